@@ -1,0 +1,172 @@
+/*
+ * poetx.h -- C ABI of the MI355X (gfx950) POET-X linear-layer library.
+ *
+ * The library evaluates the orthogonal equivalence transformation
+ *     W_eff = R * W0 * P                                   (paper Sec. 2, Eq. 1)
+ * inside a linear layer without ever forming R, P or W_eff.  R (d_in x d_in)
+ * and P (d_out x d_out) are block-diagonal matrices of b x b blocks placed
+ * under a permutation (Sec. 3, Eq. 2); each block is the truncated
+ * Cayley-Neumann series of a skew-symmetric matrix stored as its packed strict
+ * upper triangle (Sec. 3.4, Eq. 8).  W0 is frozen.
+ *
+ * Conventions shared by every call
+ * --------------------------------
+ *  - m = d_in, n = d_out, N = n_tokens.  The stored weight is W = W0^T, row
+ *    major n x m (out x in).
+ *  - Activations are FEATURE MAJOR: X is m x N, Z is n x N, row major with the
+ *    token index contiguous (leading dimension = N).  This is the column form
+ *    of Eq. 4: Z = P^T W R^T X.
+ *  - A permutation is an int32 vector pi of length d holding a bijection of
+ *    {0..d-1}.  Psi[i, pi[i]] = 1, so (Psi V)[i,:] = V[pi[i],:] and
+ *    (Psi^T V)[pi[i],:] = V[i,:]                              (Sec. 3.2, Eq. 5).
+ *    R = Psi_R^T Diag(G^0 .. G^{nb-1}) Psi_R, i.e. R[pi[i], pi[j]] = Diag[i, j].
+ *  - Blocks: nb = ceil(d / b).  If b does not divide d the last block has side
+ *    r = d - b (nb - 1); it is stored as a full b x b block whose rows/columns
+ *    >= r are those of the identity.  theta rows always hold b(b-1)/2 floats in
+ *    row-major strict-upper-triangle order, Q[i][j] = +theta for i < j; slots
+ *    of the tail block with i >= r or j >= r are ignored on input and receive a
+ *    zero gradient.
+ *  - Block storage.  dtype POETX_F32: blocks are float G[nb][b][b].
+ *    dtype POETX_BF16: blocks are bf16 E[nb][b][b] with E = G - I (the residual
+ *    keeps the small part of G that rounding G itself to bf16 would lose); the
+ *    kernels add the identity back in fp32.  poetx_cnp_build writes either.
+ *  - bf16 buffers hold raw 16-bit patterns (uint16_t); accumulation is fp32.
+ *  - All data pointers are DEVICE pointers unless marked host.  `stream` is a
+ *    hipStream_t passed as void* (NULL = the null stream).  The caller owns
+ *    every buffer; the library allocates no device memory, keeps no state
+ *    between calls, enqueues its kernels on `stream` and returns without
+ *    synchronising (poetx_perm_validate excepted).  `ws` is scratch of at least
+ *    the size the matching *_workspace_bytes call reports, 256-byte aligned.
+ *  - Output buffers must not overlap input buffers.
+ *  - Return value: POETX_OK (0) or a poetx_status error.  Arguments are checked
+ *    on the host before anything is enqueued; on error nothing was launched.
+ *    Permutation contents are NOT checked on the hot path (use
+ *    poetx_perm_validate); an out-of-range index is undefined behaviour.
+ */
+#ifndef POETX_H_
+#define POETX_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  POETX_OK = 0,
+  POETX_ERR_INVALID_ARG = 1,   /* null pointer, non-positive size, bad enum     */
+  POETX_ERR_BAD_SHAPE = 2,     /* sizes inconsistent with each other            */
+  POETX_ERR_BAD_PERM = 3,      /* poetx_perm_validate: not a bijection          */
+  POETX_ERR_UNSUPPORTED = 4,   /* valid request this build has no kernel for    */
+  POETX_ERR_WORKSPACE = 5,     /* ws is null or smaller than required           */
+  POETX_ERR_HIP = 6            /* a HIP runtime call or launch failed           */
+} poetx_status;
+
+typedef enum { POETX_F32 = 0, POETX_BF16 = 1 } poetx_dtype;
+
+/* How the block products of the Cayley-Neumann chain are multiplied.
+ * FP32: plain fp32 arithmetic.  BF16X1: operands rounded to bf16, fp32
+ * accumulation on the matrix cores (meets the bf16 tolerance, not the fp32 one). */
+typedef enum { POETX_CNP_FP32 = 0, POETX_CNP_BF16 = 1 } poetx_cnp_precision;
+
+/* One POET-X linear layer (Sec. 3.5, Eq. 10). */
+typedef struct {
+  int32_t d_in;        /* m */
+  int32_t d_out;       /* n */
+  int32_t block;       /* b, side of the orthogonal blocks                    */
+  int32_t neumann_k;   /* k: highest power kept in (I - Q)^-1 ~ sum_{i<=k} Q^i */
+  int64_t n_tokens;    /* N */
+  int32_t dtype;       /* poetx_dtype of X, W, Z, saved B, gradients, blocks   */
+  int32_t cnp_precision; /* poetx_cnp_precision used by poetx_linear_bwd_skew  */
+} poetx_linear_desc;
+
+const char* poetx_status_string(int status);
+
+/* Library version (major * 100 + minor). */
+int poetx_version(void);
+
+/* Test hook (process-wide, not for production use): on != 0 routes every call,
+ * whatever its dtype, through the plain fp32-FMA kernels instead of the
+ * matrix-core kernels, so that the two kernel families can be compared. */
+void poetx_debug_force_fma(int on);
+
+/* ---------------------------------------------------------------------------
+ * skew_symmetric + cayley_neumann (Sec. 3.4, Eq. 8-9), batched over blocks:
+ *   Q_j = skew(theta_j),  G_j = (I + Q_j)(I + Q_j + ... + Q_j^k)
+ *       = I + 2 sum_{p=1..k} Q_j^p + Q_j^{k+1}.
+ * theta : [nb][b(b-1)/2] float, nb = ceil(d / b); d gives the ragged tail.
+ * G_f32 : [nb][b][b] float, nullable.   E_bf16 : [nb][b][b] bf16 of G - I,
+ * nullable (at least one must be given).
+ * ws    : poetx_cnp_workspace_bytes(d, b) bytes.
+ */
+size_t poetx_cnp_workspace_bytes(int32_t d, int32_t b);
+int poetx_cnp_build(const float* theta, int32_t d, int32_t b, int32_t k, int32_t precision,
+                    float* G_f32, void* E_bf16, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Structured apply without materialising the orthogonal matrix (Eq. 2 with
+ * Eq. 5 and Eq. 7):
+ *   left :  out = Psi^T Diag(op(G)) Psi * V,   V and out are d x cols, leading
+ *           dimension ld >= cols (elements).          (R V, R^T X, P dZ, ...)
+ *   right:  out = V * Psi^T Diag(op(G)) Psi,   V and out are rows x d, leading
+ *           dimension ld >= d.                        (W0 P, the merge R W0 P)
+ * op(G) = G^T when transpose_G != 0.  `blocks` is G (float) or E (bf16) as the
+ * dtype says.  perm has d entries.  out must not alias V.
+ */
+int poetx_perm_blockdiag_apply_left(const void* V, void* out, int32_t d, int64_t cols, int64_t ld,
+                                    const int32_t* perm, const void* blocks, int32_t b,
+                                    int32_t transpose_G, int32_t dtype, void* stream);
+int poetx_perm_blockdiag_apply_right(const void* V, void* out, int64_t rows, int32_t d, int64_t ld,
+                                     const int32_t* perm, const void* blocks, int32_t b,
+                                     int32_t transpose_G, int32_t dtype, void* stream);
+
+/* Debug helper: checks on the device that perm is a bijection of {0..d-1}.
+ * scratch: d + 1 int32 on the device.  Synchronises `stream`. */
+int poetx_perm_validate(const int32_t* perm, int32_t d, int32_t* scratch, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * The linear layer, input-centric (Eq. 3, Eq. 4, Eq. 10).  Because gather and
+ * scatter are folded into the block kernels, W is used as stored (the
+ * pre-permuted W' of Eq. 6 is not needed) and all activations keep physical
+ * feature order:
+ *   forward : A = R^T X (mm1),  B = W A (mm2),  Z = P^T B (mm3)
+ *   backward: dB = P dZ,  dA = W^T dB  (no weight gradient),  dX = R dA
+ *             dG_P^j = B'_j dZ'_j^T, dG_R^j = X'_j dA'_j^T  (primes: rows
+ *             gathered by the side's permutation), then the chain rule through
+ *             the series and the projection onto the packed parameters.
+ * poetx_linear_workspace_bytes: scratch needed by the largest of the three.
+ */
+size_t poetx_linear_workspace_bytes(const poetx_linear_desc* desc);
+
+/* X: m x N.  W: n x m.  blocks_R / blocks_P: [ceil(m/b)][b][b], [ceil(n/b)][b][b].
+ * Z: n x N (out).  saved_B: n x N (out; the one activation the fast variant
+ * keeps for the backward pass, physical feature order). */
+int poetx_linear_fwd(const poetx_linear_desc* desc, const void* X, const void* W,
+                     const int32_t* perm_R, const int32_t* perm_P,
+                     const void* blocks_R, const void* blocks_P,
+                     void* Z, void* saved_B, void* ws, size_t ws_bytes, void* stream);
+
+/* dZ: n x N.  dX: m x N (out).  dA: m x N (out; W^T P dZ in physical order,
+ * consumed by poetx_linear_bwd_skew). */
+int poetx_linear_bwd_input(const poetx_linear_desc* desc, const void* dZ, const void* W,
+                           const int32_t* perm_R, const int32_t* perm_P,
+                           const void* blocks_R, const void* blocks_P,
+                           void* dX, void* dA, void* ws, size_t ws_bytes, void* stream);
+
+/* Gradients on the packed skew parameters of both sides (Sec. 3.4 backward
+ * display generalised to any k; Sec. 3.5 mm1/mm3 backward).
+ * theta_R: [ceil(m/b)][b(b-1)/2] float, theta_P likewise for n.
+ * dtheta_R / dtheta_P: same shapes (out); overwritten when accumulate == 0,
+ * added to otherwise. */
+int poetx_linear_bwd_skew(const poetx_linear_desc* desc, const void* X, const void* dZ,
+                          const void* saved_B, const void* dA,
+                          const int32_t* perm_R, const int32_t* perm_P,
+                          const float* theta_R, const float* theta_P,
+                          float* dtheta_R, float* dtheta_P, int32_t accumulate,
+                          void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POETX_H_ */

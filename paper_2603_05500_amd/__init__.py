@@ -1,0 +1,196 @@
+"""Thin Python binding of libpoetx.so (the C ABI declared in include/poetx.h).
+
+Argument marshalling only: every function takes torch tensors that already
+live on the GPU, passes their device pointers and the current HIP stream to
+the C entry point of the same name, and raises on a non-zero status.  No step
+of the method is computed in Python and there is no CPU fallback: if the
+library is missing, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, Structure, c_char_p, c_int, c_int32, c_int64, c_size_t, c_void_p
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libpoetx.so")
+
+F32, BF16 = 0, 1
+CNP_FP32, CNP_BF16 = 0, 1
+
+EXPORTS = (
+    "poetx_status_string", "poetx_version", "poetx_debug_force_fma",
+    "poetx_cnp_workspace_bytes", "poetx_cnp_build",
+    "poetx_perm_blockdiag_apply_left", "poetx_perm_blockdiag_apply_right", "poetx_perm_validate",
+    "poetx_linear_workspace_bytes", "poetx_linear_fwd", "poetx_linear_bwd_input", "poetx_linear_bwd_skew",
+)
+
+
+class LinearDesc(Structure):
+    _fields_ = [("d_in", c_int32), ("d_out", c_int32), ("block", c_int32), ("neumann_k", c_int32),
+                ("n_tokens", c_int64), ("dtype", c_int32), ("cnp_precision", c_int32)]
+
+
+class PoetxError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def load_library(path: str | None = None):
+    """dlopen libpoetx.so and declare its prototypes.  Raises if it is not built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    p = path or LIB_PATH
+    if not os.path.exists(p):
+        raise FileNotFoundError(f"{p} not built: run `python -m paper_2603_05500_amd.build` "
+                                "(or __graft_entry__.build()) first")
+    lib = ctypes.CDLL(p)
+    lib.poetx_status_string.restype = c_char_p
+    lib.poetx_status_string.argtypes = [c_int]
+    lib.poetx_version.restype = c_int
+    lib.poetx_debug_force_fma.restype = None
+    lib.poetx_debug_force_fma.argtypes = [c_int]
+    lib.poetx_cnp_workspace_bytes.restype = c_size_t
+    lib.poetx_cnp_workspace_bytes.argtypes = [c_int32, c_int32]
+    lib.poetx_cnp_build.restype = c_int
+    lib.poetx_cnp_build.argtypes = [c_void_p, c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p,
+                                    c_void_p, c_size_t, c_void_p]
+    for name in ("poetx_perm_blockdiag_apply_left",):
+        f = getattr(lib, name)
+        f.restype = c_int
+        f.argtypes = [c_void_p, c_void_p, c_int32, c_int64, c_int64, c_void_p, c_void_p, c_int32, c_int32,
+                      c_int32, c_void_p]
+    lib.poetx_perm_blockdiag_apply_right.restype = c_int
+    lib.poetx_perm_blockdiag_apply_right.argtypes = [c_void_p, c_void_p, c_int64, c_int32, c_int64, c_void_p,
+                                                     c_void_p, c_int32, c_int32, c_int32, c_void_p]
+    lib.poetx_perm_validate.restype = c_int
+    lib.poetx_perm_validate.argtypes = [c_void_p, c_int32, c_void_p, c_void_p]
+    lib.poetx_linear_workspace_bytes.restype = c_size_t
+    lib.poetx_linear_workspace_bytes.argtypes = [POINTER(LinearDesc)]
+    lib.poetx_linear_fwd.restype = c_int
+    lib.poetx_linear_fwd.argtypes = [POINTER(LinearDesc)] + [c_void_p] * 9 + [c_size_t, c_void_p]
+    lib.poetx_linear_bwd_input.restype = c_int
+    lib.poetx_linear_bwd_input.argtypes = [POINTER(LinearDesc)] + [c_void_p] * 9 + [c_size_t, c_void_p]
+    lib.poetx_linear_bwd_skew.restype = c_int
+    lib.poetx_linear_bwd_skew.argtypes = [POINTER(LinearDesc)] + [c_void_p] * 10 + [c_int32, c_void_p, c_size_t,
+                                                                                   c_void_p]
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().poetx_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise PoetxError(status, where)
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return c_void_p(t.data_ptr())
+
+
+def _stream():
+    return c_void_p(_torch().cuda.current_stream().cuda_stream)
+
+
+def dtype_code(t) -> int:
+    torch = _torch()
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def make_desc(d_in, d_out, block, neumann_k, n_tokens, dtype, cnp_precision=None) -> LinearDesc:
+    if cnp_precision is None:
+        cnp_precision = CNP_FP32 if dtype == F32 else CNP_BF16
+    return LinearDesc(d_in, d_out, block, neumann_k, n_tokens, dtype, cnp_precision)
+
+
+def poetx_debug_force_fma(on: bool):
+    load_library().poetx_debug_force_fma(1 if on else 0)
+
+
+def poetx_cnp_workspace_bytes(d: int, b: int) -> int:
+    return load_library().poetx_cnp_workspace_bytes(d, b)
+
+
+def poetx_linear_workspace_bytes(desc: LinearDesc) -> int:
+    return load_library().poetx_linear_workspace_bytes(ctypes.byref(desc))
+
+
+def poetx_cnp_build(theta, d, b, k, precision, G_f32=None, E_bf16=None, ws=None):
+    lib = load_library()
+    _check(lib.poetx_cnp_build(_ptr(theta), d, b, k, precision, _ptr(G_f32), _ptr(E_bf16), _ptr(ws),
+                               ws.numel() * ws.element_size() if ws is not None else 0, _stream()),
+           "poetx_cnp_build")
+
+
+def poetx_perm_blockdiag_apply_left(V, out, perm, blocks, b, transpose_G):
+    lib = load_library()
+    d, cols = V.shape
+    _check(lib.poetx_perm_blockdiag_apply_left(_ptr(V), _ptr(out), d, cols, V.stride(0), _ptr(perm), _ptr(blocks),
+                                               b, int(bool(transpose_G)), dtype_code(V), _stream()),
+           "poetx_perm_blockdiag_apply_left")
+
+
+def poetx_perm_blockdiag_apply_right(V, out, perm, blocks, b, transpose_G):
+    lib = load_library()
+    rows, d = V.shape
+    _check(lib.poetx_perm_blockdiag_apply_right(_ptr(V), _ptr(out), rows, d, V.stride(0), _ptr(perm), _ptr(blocks),
+                                                b, int(bool(transpose_G)), dtype_code(V), _stream()),
+           "poetx_perm_blockdiag_apply_right")
+
+
+def poetx_perm_validate(perm, scratch) -> bool:
+    """True if perm is a bijection; False if the library reports BAD_PERM."""
+    lib = load_library()
+    rc = lib.poetx_perm_validate(_ptr(perm), perm.numel(), _ptr(scratch), _stream())
+    if rc == 3:
+        return False
+    _check(rc, "poetx_perm_validate")
+    return True
+
+
+def _ws_bytes(ws):
+    return ws.numel() * ws.element_size()
+
+
+def poetx_linear_fwd(desc, X, W, perm_R, perm_P, blocks_R, blocks_P, Z, saved_B, ws):
+    lib = load_library()
+    _check(lib.poetx_linear_fwd(ctypes.byref(desc), _ptr(X), _ptr(W), _ptr(perm_R), _ptr(perm_P), _ptr(blocks_R),
+                                _ptr(blocks_P), _ptr(Z), _ptr(saved_B), _ptr(ws), _ws_bytes(ws), _stream()),
+           "poetx_linear_fwd")
+
+
+def poetx_linear_bwd_input(desc, dZ, W, perm_R, perm_P, blocks_R, blocks_P, dX, dA, ws):
+    lib = load_library()
+    _check(lib.poetx_linear_bwd_input(ctypes.byref(desc), _ptr(dZ), _ptr(W), _ptr(perm_R), _ptr(perm_P),
+                                      _ptr(blocks_R), _ptr(blocks_P), _ptr(dX), _ptr(dA), _ptr(ws), _ws_bytes(ws),
+                                      _stream()),
+           "poetx_linear_bwd_input")
+
+
+def poetx_linear_bwd_skew(desc, X, dZ, saved_B, dA, perm_R, perm_P, theta_R, theta_P, dtheta_R, dtheta_P,
+                          accumulate, ws):
+    lib = load_library()
+    _check(lib.poetx_linear_bwd_skew(ctypes.byref(desc), _ptr(X), _ptr(dZ), _ptr(saved_B), _ptr(dA), _ptr(perm_R),
+                                     _ptr(perm_P), _ptr(theta_R), _ptr(theta_P), _ptr(dtheta_R), _ptr(dtheta_P),
+                                     int(bool(accumulate)), _ptr(ws), _ws_bytes(ws), _stream()),
+           "poetx_linear_bwd_skew")

@@ -1,0 +1,211 @@
+// C-ABI entry points: host-side argument checks and kernel dispatch.
+// Every step of the path runs in the kernels of this library; this file only
+// validates, carves the workspace and enqueues.
+#include <atomic>
+
+#include "poetx_kernels.h"
+
+using namespace poetx;
+
+namespace {
+
+std::atomic<int> g_force_fma{0};
+
+inline bool use_mfma(int dtype) { return dtype == POETX_BF16 && !g_force_fma.load(); }
+inline size_t esize(int dtype) { return dtype == POETX_F32 ? 4 : 2; }
+inline bool dtype_ok(int dtype) { return dtype == POETX_F32 || dtype == POETX_BF16; }
+inline bool overlap(const void* a, size_t na, const void* b, size_t nb) {
+  const char* x = (const char*)a;
+  const char* y = (const char*)b;
+  return x < y + nb && y < x + na;
+}
+
+int check_desc(const poetx_linear_desc* d) {
+  if (!d) return POETX_ERR_INVALID_ARG;
+  if (d->d_in <= 0 || d->d_out <= 0 || d->block <= 0 || d->neumann_k < 1 || d->n_tokens <= 0)
+    return POETX_ERR_INVALID_ARG;
+  if (!dtype_ok(d->dtype)) return POETX_ERR_INVALID_ARG;
+  if (d->cnp_precision != POETX_CNP_FP32 && d->cnp_precision != POETX_CNP_BF16) return POETX_ERR_INVALID_ARG;
+  if (d->block > d->d_in || d->block > d->d_out) return POETX_ERR_BAD_SHAPE;
+  if (d->n_tokens >= (1ll << 31) || (i64)d->n_tokens * (d->d_in > d->d_out ? d->d_in : d->d_out) >= (1ll << 40))
+    return POETX_ERR_UNSUPPORTED;
+  return POETX_OK;
+}
+
+size_t cnp_bwd_ws_floats(int d, int b) { return (size_t)5 * ceil_div(d, b) * b * b; }
+
+void apply_left_dispatch(int dtype, const void* V, void* out, int d, i64 cols, i64 ld, const int32_t* perm,
+                         const void* blocks, int b, int trans, hipStream_t st) {
+  if (use_mfma(dtype) && mfma_apply_left_supported(d, cols, ld, b))
+    mfma_apply_left(V, out, d, cols, ld, perm, blocks, b, trans, st);
+  else
+    fma_apply_left(dtype, V, out, d, cols, ld, perm, blocks, b, trans, st);
+}
+
+void dense_dispatch(int dtype, int trans_w, const void* W, int n, int m, const void* act, void* out, i64 N,
+                    hipStream_t st) {
+  if (use_mfma(dtype) && mfma_dense_supported(n, m, N)) mfma_dense(trans_w, W, n, m, act, out, N, st);
+  else fma_dense(dtype, trans_w, W, n, m, act, out, N, st);
+}
+
+size_t blockgrad_ws_bytes(int dtype, int d, i64 N, int b) {
+  if (dtype == POETX_BF16 && mfma_blockgrad_supported(d, N, b)) return align256(mfma_blockgrad_workspace_bytes(d, N, b));
+  return 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* poetx_status_string(int s) {
+  switch (s) {
+    case POETX_OK: return "ok";
+    case POETX_ERR_INVALID_ARG: return "invalid argument";
+    case POETX_ERR_BAD_SHAPE: return "inconsistent shapes";
+    case POETX_ERR_BAD_PERM: return "not a permutation";
+    case POETX_ERR_UNSUPPORTED: return "unsupported configuration";
+    case POETX_ERR_WORKSPACE: return "workspace missing or too small";
+    case POETX_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int poetx_version(void) { return 100; }
+
+// Test hook: path != 0 forces the plain fp32-FMA kernels for every dtype.
+void poetx_debug_force_fma(int on) { g_force_fma.store(on ? 1 : 0); }
+
+size_t poetx_cnp_workspace_bytes(int32_t d, int32_t b) {
+  if (d <= 0 || b <= 0) return 0;
+  return align256((size_t)2 * ceil_div(d, b) * b * b * sizeof(float));
+}
+
+int poetx_cnp_build(const float* theta, int32_t d, int32_t b, int32_t k, int32_t precision, float* G_f32,
+                    void* E_bf16, void* ws, size_t ws_bytes, void* stream) {
+  if (!theta || (!G_f32 && !E_bf16) || d <= 0 || b <= 0 || k < 1) return POETX_ERR_INVALID_ARG;
+  if (precision != POETX_CNP_FP32 && precision != POETX_CNP_BF16) return POETX_ERR_INVALID_ARG;
+  if (b > d) return POETX_ERR_BAD_SHAPE;
+  if (!ws || ws_bytes < poetx_cnp_workspace_bytes(d, b)) return POETX_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  if (precision == POETX_CNP_BF16 && !g_force_fma.load() && mfma_cnp_supported(b))
+    mfma_cnp_build(theta, d, b, k, G_f32, E_bf16, (float*)ws, st);
+  else
+    fma_cnp_build(theta, d, b, k, G_f32, E_bf16, (float*)ws, st);
+  return launch_status();
+}
+
+int poetx_perm_blockdiag_apply_left(const void* V, void* out, int32_t d, int64_t cols, int64_t ld,
+                                    const int32_t* perm, const void* blocks, int32_t b, int32_t transpose_G,
+                                    int32_t dtype, void* stream) {
+  if (!V || !out || !perm || !blocks || d <= 0 || cols <= 0 || b <= 0 || !dtype_ok(dtype)) return POETX_ERR_INVALID_ARG;
+  if (ld < cols || b > d) return POETX_ERR_BAD_SHAPE;
+  if (cols >= (1ll << 31)) return POETX_ERR_UNSUPPORTED;
+  size_t bytes = (size_t)d * ld * esize(dtype);
+  if (overlap(V, bytes, out, bytes)) return POETX_ERR_INVALID_ARG;
+  apply_left_dispatch(dtype, V, out, d, cols, ld, perm, blocks, b, transpose_G != 0, (hipStream_t)stream);
+  return launch_status();
+}
+
+int poetx_perm_blockdiag_apply_right(const void* V, void* out, int64_t rows, int32_t d, int64_t ld,
+                                     const int32_t* perm, const void* blocks, int32_t b, int32_t transpose_G,
+                                     int32_t dtype, void* stream) {
+  if (!V || !out || !perm || !blocks || d <= 0 || rows <= 0 || b <= 0 || !dtype_ok(dtype)) return POETX_ERR_INVALID_ARG;
+  if (ld < d || b > d) return POETX_ERR_BAD_SHAPE;
+  if (rows >= (1ll << 31)) return POETX_ERR_UNSUPPORTED;
+  size_t bytes = (size_t)rows * ld * esize(dtype);
+  if (overlap(V, bytes, out, bytes)) return POETX_ERR_INVALID_ARG;
+  fma_apply_right(dtype, V, out, rows, d, ld, perm, blocks, b, transpose_G != 0, (hipStream_t)stream);
+  return launch_status();
+}
+
+int poetx_perm_validate(const int32_t* perm, int32_t d, int32_t* scratch, void* stream) {
+  if (!perm || !scratch || d <= 0) return POETX_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  perm_validate_launch(perm, d, scratch, st);
+  int32_t bad = 0;
+  if (hipMemcpyAsync(&bad, scratch + d, sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess) return POETX_ERR_HIP;
+  if (hipStreamSynchronize(st) != hipSuccess) return POETX_ERR_HIP;
+  return bad ? POETX_ERR_BAD_PERM : POETX_OK;
+}
+
+size_t poetx_linear_workspace_bytes(const poetx_linear_desc* desc) {
+  if (check_desc(desc) != POETX_OK) return 0;
+  size_t es = esize(desc->dtype);
+  size_t N = (size_t)desc->n_tokens;
+  size_t fwd = align256((size_t)desc->d_in * N * es);   // A = R^T X
+  size_t bwi = align256((size_t)desc->d_out * N * es);  // dB = P dZ
+  int dmax = desc->d_in > desc->d_out ? desc->d_in : desc->d_out;
+  size_t bg_in = blockgrad_ws_bytes(desc->dtype, desc->d_in, desc->n_tokens, desc->block);
+  size_t bg_out = blockgrad_ws_bytes(desc->dtype, desc->d_out, desc->n_tokens, desc->block);
+  size_t skew = align256(cnp_bwd_ws_floats(dmax, desc->block) * sizeof(float)) + (bg_in > bg_out ? bg_in : bg_out);
+  size_t w = fwd > bwi ? fwd : bwi;
+  return w > skew ? w : skew;
+}
+
+int poetx_linear_fwd(const poetx_linear_desc* desc, const void* X, const void* W, const int32_t* perm_R,
+                     const int32_t* perm_P, const void* blocks_R, const void* blocks_P, void* Z, void* saved_B,
+                     void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (!X || !W || !perm_R || !perm_P || !blocks_R || !blocks_P || !Z || !saved_B) return POETX_ERR_INVALID_ARG;
+  if (!ws || ws_bytes < poetx_linear_workspace_bytes(desc)) return POETX_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  const int m = desc->d_in, n = desc->d_out, b = desc->block, dt = desc->dtype;
+  const i64 N = desc->n_tokens;
+  void* A = ws;
+  apply_left_dispatch(dt, X, A, m, N, N, perm_R, blocks_R, b, 1, st);        // mm1: A = R^T X
+  dense_dispatch(dt, 0, W, n, m, A, saved_B, N, st);                        // mm2: B = W A
+  apply_left_dispatch(dt, saved_B, Z, n, N, N, perm_P, blocks_P, b, 1, st);  // mm3: Z = P^T B
+  return launch_status();
+}
+
+int poetx_linear_bwd_input(const poetx_linear_desc* desc, const void* dZ, const void* W, const int32_t* perm_R,
+                           const int32_t* perm_P, const void* blocks_R, const void* blocks_P, void* dX, void* dA,
+                           void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (!dZ || !W || !perm_R || !perm_P || !blocks_R || !blocks_P || !dX || !dA) return POETX_ERR_INVALID_ARG;
+  if (!ws || ws_bytes < poetx_linear_workspace_bytes(desc)) return POETX_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  const int m = desc->d_in, n = desc->d_out, b = desc->block, dt = desc->dtype;
+  const i64 N = desc->n_tokens;
+  void* dB = ws;
+  apply_left_dispatch(dt, dZ, dB, n, N, N, perm_P, blocks_P, b, 0, st);  // dB = P dZ
+  dense_dispatch(dt, 1, W, n, m, dB, dA, N, st);                        // dA = W^T dB
+  apply_left_dispatch(dt, dA, dX, m, N, N, perm_R, blocks_R, b, 0, st);  // dX = R dA
+  return launch_status();
+}
+
+int poetx_linear_bwd_skew(const poetx_linear_desc* desc, const void* X, const void* dZ, const void* saved_B,
+                          const void* dA, const int32_t* perm_R, const int32_t* perm_P, const float* theta_R,
+                          const float* theta_P, float* dtheta_R, float* dtheta_P, int32_t accumulate, void* ws,
+                          size_t ws_bytes, void* stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (!X || !dZ || !saved_B || !dA || !perm_R || !perm_P || !theta_R || !theta_P || !dtheta_R || !dtheta_P)
+    return POETX_ERR_INVALID_ARG;
+  if (!ws || ws_bytes < poetx_linear_workspace_bytes(desc)) return POETX_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  const int m = desc->d_in, n = desc->d_out, b = desc->block, dt = desc->dtype, k = desc->neumann_k;
+  const i64 N = desc->n_tokens;
+  const int dmax = m > n ? m : n;
+  float* dG = (float*)ws;
+  float* chain = dG + (size_t)ceil_div(dmax, b) * b * b;
+  void* bg_ws = (char*)ws + align256(cnp_bwd_ws_floats(dmax, b) * sizeof(float));
+  const bool fast_cnp = desc->cnp_precision == POETX_CNP_BF16 && !g_force_fma.load() && mfma_cnp_supported(b);
+  for (int side = 0; side < 2; ++side) {
+    const void* U = side == 0 ? saved_B : X;   // mm3 backward: dG_P = B' dZ'^T; mm1 backward: dG_R = X' dA'^T
+    const void* V = side == 0 ? dZ : dA;
+    const int d = side == 0 ? n : m;
+    const int32_t* perm = side == 0 ? perm_P : perm_R;
+    const float* theta = side == 0 ? theta_P : theta_R;
+    float* dtheta = side == 0 ? dtheta_P : dtheta_R;
+    if (use_mfma(dt) && mfma_blockgrad_supported(d, N, b)) mfma_blockgrad(U, V, d, N, perm, b, dG, bg_ws, st);
+    else fma_blockgrad(dt, U, V, d, N, perm, b, dG, st);
+    if (fast_cnp) mfma_cnp_bwd(theta, dG, d, b, k, dtheta, accumulate != 0, chain, st);
+    else fma_cnp_bwd(theta, dG, d, b, k, dtheta, accumulate != 0, chain, st);
+  }
+  return launch_status();
+}
+
+}  // extern "C"

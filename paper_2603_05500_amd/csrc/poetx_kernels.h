@@ -1,0 +1,47 @@
+// Internal launch interface between the C-ABI layer and the kernel files.
+// Every launcher enqueues on `st` and returns; shapes were validated by the caller.
+#pragma once
+
+#include "poetx_common.h"
+
+namespace poetx {
+
+// ---- plain fp32-FMA path (fma_kernels.hip): any dtype, any block size ---------------
+// out = op(W) * act:  W is n x m row major.  trans_w == 0: out (n x N) = W act (m x N);
+// trans_w == 1: out (m x N) = W^T act (n x N).
+void fma_dense(int dtype, int trans_w, const void* W, int n, int m, const void* act, void* out,
+               i64 N, hipStream_t st);
+void fma_apply_left(int dtype, const void* V, void* out, int d, i64 cols, i64 ld, const int32_t* perm,
+                    const void* blocks, int b, int transpose_G, hipStream_t st);
+void fma_apply_right(int dtype, const void* V, void* out, i64 rows, int d, i64 ld, const int32_t* perm,
+                     const void* blocks, int b, int transpose_G, hipStream_t st);
+// dG[j] = U'_j V'_j^T with rows of U and V (d x N each) gathered by perm; dG is [nb][b][b] float.
+void fma_blockgrad(int dtype, const void* U, const void* V, int d, i64 N, const int32_t* perm, int b,
+                   float* dG, hipStream_t st);
+// ws: 2 * nb*b*b floats.
+void fma_cnp_build(const float* theta, int d, int b, int k, float* G_f32, void* E_bf16, float* ws,
+                   hipStream_t st);
+// dG -> dtheta.  ws: 4 * nb*b*b floats.
+void fma_cnp_bwd(const float* theta, const float* dG, int d, int b, int k, float* dtheta, int accumulate,
+                 float* ws, hipStream_t st);
+
+void perm_validate_launch(const int32_t* perm, int d, int32_t* scratch, hipStream_t st);
+
+// ---- matrix-core path for bf16 (mfma_*.hip) -------------------------------------------
+bool mfma_dense_supported(int n, int m, i64 N);
+void mfma_dense(int trans_w, const void* W, int n, int m, const void* act, void* out, i64 N,
+                hipStream_t st);
+bool mfma_apply_left_supported(int d, i64 cols, i64 ld, int b);
+void mfma_apply_left(const void* V, void* out, int d, i64 cols, i64 ld, const int32_t* perm,
+                     const void* E, int b, int transpose_G, hipStream_t st);
+bool mfma_blockgrad_supported(int d, i64 N, int b);
+size_t mfma_blockgrad_workspace_bytes(int d, i64 N, int b);
+void mfma_blockgrad(const void* U, const void* V, int d, i64 N, const int32_t* perm, int b, float* dG,
+                    void* ws, hipStream_t st);
+bool mfma_cnp_supported(int b);
+void mfma_cnp_build(const float* theta, int d, int b, int k, float* G_f32, void* E_bf16, float* ws,
+                    hipStream_t st);
+void mfma_cnp_bwd(const float* theta, const float* dG, int d, int b, int k, float* dtheta, int accumulate,
+                  float* ws, hipStream_t st);
+
+}  // namespace poetx

@@ -1,0 +1,72 @@
+"""CPU-side checks of the C ABI: the library loads, exports what the header
+declares, and rejects bad arguments on the host before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2603_05500_amd as px
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def clib():
+    if not os.path.exists(px.LIB_PATH):
+        from paper_2603_05500_amd import build
+        build.build()
+    return px.load_library()
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "poetx.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(poetx_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_exported(clib):
+    syms = header_symbols()
+    assert len(syms) >= 12
+    for s in syms:
+        assert hasattr(clib, s), f"{s} declared in poetx.h but not exported"
+    assert set(px.EXPORTS) == set(syms)
+
+
+def test_status_strings(clib):
+    assert px.status_string(0) == "ok"
+    for s in range(1, 7):
+        assert px.status_string(s) not in ("ok", "unknown status")
+    assert px.status_string(99) == "unknown status"
+    assert clib.poetx_version() >= 100
+
+
+def test_workspace_queries(clib):
+    assert px.poetx_cnp_workspace_bytes(256, 32) >= 2 * 8 * 32 * 32 * 4
+    assert px.poetx_cnp_workspace_bytes(0, 32) == 0
+    d = px.make_desc(256, 256, 32, 4, 512, px.F32)
+    assert px.poetx_linear_workspace_bytes(d) >= 256 * 512 * 4
+    bad = px.make_desc(256, 256, 32, 0, 512, px.F32)  # k < 1
+    assert px.poetx_linear_workspace_bytes(bad) == 0
+
+
+def test_host_argument_checks(clib):
+    """Null pointers and bad sizes are refused on the host (no device needed)."""
+    fake = ctypes.c_void_p(0x1000)  # never dereferenced: checks fail first
+    assert clib.poetx_cnp_build(None, 64, 32, 3, 0, fake, None, fake, 1 << 20, None) == 1
+    assert clib.poetx_cnp_build(fake, 64, 32, 0, 0, fake, None, fake, 1 << 20, None) == 1   # k < 1
+    assert clib.poetx_cnp_build(fake, 16, 32, 3, 0, fake, None, fake, 1 << 20, None) == 2   # b > d
+    assert clib.poetx_cnp_build(fake, 64, 32, 3, 0, fake, None, fake, 16, None) == 5        # workspace
+    assert clib.poetx_cnp_build(fake, 64, 32, 3, 7, fake, None, fake, 1 << 20, None) == 1   # precision
+    assert clib.poetx_perm_blockdiag_apply_left(fake, fake, 64, 8, 8, fake, fake, 32, 0, 0, None) == 1  # alias
+    assert clib.poetx_perm_blockdiag_apply_left(fake, ctypes.c_void_p(0x100000), 64, 8, 4, fake, fake, 32, 0, 0,
+                                                None) == 2  # ld < cols
+    assert clib.poetx_perm_blockdiag_apply_right(None, fake, 8, 64, 64, fake, fake, 32, 0, 0, None) == 1
+    d = px.make_desc(256, 256, 32, 4, 512, px.F32)
+    args = [fake] * 9
+    assert clib.poetx_linear_fwd(ctypes.byref(d), *args, 0, None) == 5
+    assert clib.poetx_linear_fwd(None, *args, 1 << 30, None) == 1
+    d2 = px.make_desc(256, 256, 32, 4, 512, 9)
+    assert clib.poetx_linear_bwd_input(ctypes.byref(d2), *args, 1 << 30, None) == 1
+    d3 = px.make_desc(256, 16, 32, 4, 512, px.F32)
+    assert clib.poetx_linear_bwd_skew(ctypes.byref(d3), *([fake] * 10), 0, fake, 1 << 30, None) == 2

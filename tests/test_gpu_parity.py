@@ -1,0 +1,200 @@
+"""GPU parity: the HIP library against the fp64 oracle, element by element, on
+seeded inputs.  Tolerances (max |gpu - ref| / max |ref| per tensor): 1e-4 for
+fp32 tensors, 2e-2 for bf16 tensors; index work is bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import poetx_oracle as orc
+from workloads import get_config, draw_projection, round_bf16, round_f32
+from tests.harness import TOL, build_blocks, rel_err, run_layer, tdtype, to_dev, to_np, ws_tensor
+
+pytestmark = pytest.mark.gpu
+RNG = lambda s: np.random.Generator(np.random.PCG64(s))
+
+
+def draw_theta(rng, d, b, sigma):
+    nb = orc.n_blocks(d, b)
+    return round_f32(rng.standard_normal((nb, b * (b - 1) // 2)) * sigma)
+
+
+# ------------------------------------------------------------------ cnp_build
+@pytest.mark.parametrize("d,b,k", [(64, 32, 3), (256, 32, 4), (96, 64, 4), (1376, 64, 4), (512, 256, 5),
+                                   (1024, 512, 5), (40, 8, 1), (48, 16, 2)])
+@pytest.mark.parametrize("precision", ["fp32", "bf16"])
+def test_cnp_build(lib, d, b, k, precision):
+    rng = RNG(1000 + d + b + k)
+    theta = draw_theta(rng, d, b, 0.01 if b < 256 else 0.005)
+    th = to_dev(theta, torch.float32)
+    nb = theta.shape[0]
+    G = torch.empty((nb, b, b), dtype=torch.float32, device="cuda")
+    E = torch.empty((nb, b, b), dtype=torch.bfloat16, device="cuda")
+    ws = ws_tensor(lib.poetx_cnp_workspace_bytes(d, b))
+    lib.poetx_cnp_build(th, d, b, k, lib.CNP_FP32 if precision == "fp32" else lib.CNP_BF16, G, E, ws)
+    torch.cuda.synchronize()
+    ref = orc.cnp(orc.skew_from_packed(theta, b, d), k)
+    tol = 1e-4 if precision == "fp32" else 2e-2
+    assert rel_err(to_np(G), ref) <= (1e-6 if precision == "fp32" else tol)
+    eye = np.eye(b)
+    # the residual must keep the small part of G: compare G - I on its own scale
+    assert rel_err(to_np(G) - eye, ref - eye) <= tol
+    assert rel_err(to_np(E), ref - eye) <= 2e-2
+    r = orc.tail_side(d, b)
+    if r < b:  # identity padding of the ragged tail block, exactly
+        Gt = to_np(G)[-1]
+        assert np.array_equal(Gt[r:, :], eye[r:, :]) and np.array_equal(Gt[:, r:], eye[:, r:])
+
+
+# ------------------------------------------------------------------ structured apply
+APPLY_SHAPES = [(64, 32, 48), (256, 32, 512), (96, 64, 100), (1376, 64, 1024), (160, 64, 333), (512, 256, 640),
+                (40, 8, 7)]
+
+
+@pytest.mark.parametrize("d,b,cols", APPLY_SHAPES)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("transpose", [False, True])
+def test_apply_left(lib, d, b, cols, dtype, transpose):
+    rng = RNG(2000 + d + b + cols)
+    rnd = round_f32 if dtype == "f32" else round_bf16
+    theta = draw_theta(rng, d, b, 0.02)
+    V = rnd(rng.standard_normal((d, cols)))
+    pi = rng.permutation(d).astype(np.int32)
+    blocks, G = build_blocks(theta, d, b, 4, dtype, lib.CNP_FP32)
+    Vd = to_dev(V, tdtype(dtype))
+    out = torch.empty_like(Vd)
+    lib.poetx_perm_blockdiag_apply_left(Vd, out, torch.from_numpy(pi).cuda(), blocks, b, transpose)
+    torch.cuda.synchronize()
+    G_used = G if dtype == "f32" else to_np(blocks) + np.eye(b)  # the blocks the kernel was given
+    ref = orc.apply_left(V, pi, G_used, transpose)
+    assert rel_err(to_np(out), ref) <= TOL[dtype]
+    ref_exactG = orc.apply_left(V, pi, orc.cnp(orc.skew_from_packed(theta, b, d), 4), transpose)
+    assert rel_err(to_np(out), ref_exactG) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("d,b,rows", [(64, 32, 48), (96, 64, 130), (1376, 64, 512), (512, 256, 300), (40, 8, 5)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("transpose", [False, True])
+def test_apply_right(lib, d, b, rows, dtype, transpose):
+    rng = RNG(3000 + d + b + rows)
+    rnd = round_f32 if dtype == "f32" else round_bf16
+    theta = draw_theta(rng, d, b, 0.02)
+    V = rnd(rng.standard_normal((rows, d)))
+    pi = rng.permutation(d).astype(np.int32)
+    blocks, G = build_blocks(theta, d, b, 4, dtype, lib.CNP_FP32)
+    Vd = to_dev(V, tdtype(dtype))
+    out = torch.empty_like(Vd)
+    lib.poetx_perm_blockdiag_apply_right(Vd, out, torch.from_numpy(pi).cuda(), blocks, b, transpose)
+    torch.cuda.synchronize()
+    ref = orc.apply_right(V, pi, orc.cnp(orc.skew_from_packed(theta, b, d), 4), transpose)
+    assert rel_err(to_np(out), ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("d,b,cols", [(256, 32, 512), (1376, 64, 256), (1024, 256, 512), (96, 64, 77)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_apply_indexing_bit_exact(lib, d, b, cols, dtype):
+    """Blocks that are themselves permutation matrices make the whole apply a pure row
+    permutation; on small-integer data every product and sum is exact, so the result must
+    equal numpy index arithmetic bit for bit (gather, block offsets, scatter)."""
+    rng = RNG(4000 + d + b)
+    nb = orc.n_blocks(d, b)
+    r = orc.tail_side(d, b)
+    G = np.zeros((nb, b, b))
+    for j in range(nb):
+        s = b if j < nb - 1 else r
+        sig = rng.permutation(s)
+        G[j, np.arange(s), sig] = 1.0
+        G[j, np.arange(s, b), np.arange(s, b)] = 1.0
+    V = rng.integers(-64, 65, size=(d, cols)).astype(np.float64)
+    pi = rng.permutation(d).astype(np.int32)
+    blocks = to_dev(G if dtype == "f32" else G - np.eye(b), tdtype(dtype))
+    Vd = to_dev(V, tdtype(dtype))
+    for transpose in (False, True):
+        out = torch.empty_like(Vd)
+        lib.poetx_perm_blockdiag_apply_left(Vd, out, torch.from_numpy(pi).cuda(), blocks, b, transpose)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(out), orc.apply_left(V, pi, G, transpose))
+    # identity blocks: gather followed by scatter is the identity map, bit for bit
+    eye = np.broadcast_to(np.eye(b), (nb, b, b)).copy()
+    blocks = to_dev(eye if dtype == "f32" else eye * 0, tdtype(dtype))
+    Vr = to_dev((round_f32 if dtype == "f32" else round_bf16)(rng.standard_normal((d, cols))), tdtype(dtype))
+    out = torch.empty_like(Vr)
+    lib.poetx_perm_blockdiag_apply_left(Vr, out, torch.from_numpy(pi).cuda(), blocks, b, True)
+    torch.cuda.synchronize()
+    assert torch.equal(out, Vr)
+
+
+def test_perm_validate(lib):
+    rng = RNG(5)
+    d = 1000
+    pi = rng.permutation(d).astype(np.int32)
+    scratch = torch.empty(d + 1, dtype=torch.int32, device="cuda")
+    assert lib.poetx_perm_validate(torch.from_numpy(pi).cuda(), scratch)
+    bad = pi.copy()
+    bad[3] = bad[4]
+    assert not lib.poetx_perm_validate(torch.from_numpy(bad).cuda(), scratch)
+    bad = pi.copy()
+    bad[0] = d
+    assert not lib.poetx_perm_validate(torch.from_numpy(bad).cuda(), scratch)
+
+
+# ------------------------------------------------------------------ whole layer, configs 1 and 2
+def check_layer(res, ref, pi_P, dtype):
+    tol = TOL[dtype]
+    errs = {}
+    B_ref = np.empty_like(ref["Bp"])
+    B_ref[pi_P, :] = ref["Bp"]  # the library keeps B in physical feature order
+    errs["G_R"] = rel_err(res["G_R"], ref["G_R"])
+    errs["G_P"] = rel_err(res["G_P"], ref["G_P"])
+    errs["Z"] = rel_err(res["Z"], ref["Z"])
+    errs["B"] = rel_err(res["B"], B_ref)
+    errs["dX"] = rel_err(res["dX"], ref["dX"])
+    errs["dtheta_R"] = rel_err(res["dtheta_R"], ref["dtheta_R"])
+    errs["dtheta_P"] = rel_err(res["dtheta_P"], ref["dtheta_P"])
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, f"over tolerance {tol}: {bad} (all: {errs})"
+    return errs
+
+
+def test_config1_fp32_layer(lib):
+    cfg = get_config(1)
+    data = draw_projection(cfg, 0)
+    res = run_layer(data, "f32")
+    ref = orc.linear_fwd_bwd_from_theta(data["X"], data["dZ"], data["W"], data["pi_R"], data["pi_P"],
+                                        data["theta_R"], data["theta_P"], data["b"], data["k"])
+    check_layer(res, ref, data["pi_P"], "f32")
+
+
+@pytest.mark.parametrize("proj", range(7))
+def test_config2_bf16_layer(lib, proj):
+    cfg = get_config(2)
+    data = draw_projection(cfg, proj)
+    res = run_layer(data, "bf16")
+    ref = orc.linear_fwd_bwd_from_theta(data["X"], data["dZ"], data["W"], data["pi_R"], data["pi_P"],
+                                        data["theta_R"], data["theta_P"], data["b"], data["k"])
+    check_layer(res, ref, data["pi_P"], "bf16")
+    # ragged tail: unused parameter slots get exactly zero gradient
+    for side, d in (("dtheta_R", data["m"]), ("dtheta_P", data["n"])):
+        r = orc.tail_side(d, data["b"])
+        if r < data["b"]:
+            iu, ju = np.triu_indices(data["b"], k=1)
+            assert np.all(res[side][-1, (iu >= r) | (ju >= r)] == 0)
+
+
+def test_config2_fp32_storage_and_accumulate(lib):
+    """Same shapes in fp32 storage (tight tolerance) and the accumulate flag of bwd_skew."""
+    cfg = get_config(2)
+    data = draw_projection(cfg, 6)  # down: 512 x 1376, ragged input side
+    for key in ("X", "dZ", "W"):
+        data[key] = round_f32(data[key])
+    res = run_layer(data, "f32")
+    ref = orc.linear_fwd_bwd_from_theta(data["X"], data["dZ"], data["W"], data["pi_R"], data["pi_P"],
+                                        data["theta_R"], data["theta_P"], data["b"], data["k"])
+    check_layer(res, ref, data["pi_P"], "f32")
+    dev = res["dev"]
+    dth_R = torch.ones_like(dev["th_R"])
+    dth_P = torch.ones_like(dev["th_P"])
+    lib.poetx_linear_bwd_skew(dev["desc"], dev["X"], dev["dZ"], dev["B"], dev["dA"], dev["pi_R"], dev["pi_P"],
+                              dev["th_R"], dev["th_P"], dth_R, dth_P, True, dev["ws"])
+    torch.cuda.synchronize()
+    assert rel_err(to_np(dth_R) - 1.0, ref["dtheta_R"]) <= 1e-4
+    assert rel_err(to_np(dth_P) - 1.0, ref["dtheta_P"]) <= 1e-4
