@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the POET-X linear hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one Llama-8B-shaped decoder
+layer: for each of the seven projections, Cayley-Neumann build of both block
+sets, forward, backward to the input and backward to the packed skew
+parameters (the `fast` variant, which keeps B).  All inputs are synthetic,
+seeded and resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama8b-b256",
+                    help="llama8b-b256 (default, the metric's configuration), llama8b-b512, llama3b, llama1b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-tokens", type=int, default=128, help="tokens in the oracle's timed sample")
+    return ap.parse_args()
+
+
+def layer_flops(cfg):
+    """Algorithmic flops of one step: two dense products, six block products per side,
+    and the series (k products forward, 3k-1 backward per block)."""
+    N, b, k = cfg.n_tokens, cfg.block, cfg.neumann_k
+    dense = block = cnp = 0.0
+    for p in cfg.projections:
+        m, n = p.d_in, p.d_out
+        dense += 4.0 * N * m * n
+        block += 6.0 * N * (m + n) * b
+        nb = -(-m // b) + -(-n // b)
+        cnp += nb * (k + 3 * k - 1) * 2.0 * b ** 3
+    return dense, block, cnp
+
+
+def make_inputs(cfg, torch):
+    """Seeded device-side draws with the distributions of the configuration."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(20260305 + 1000 * cfg.index)
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    N, b = cfg.n_tokens, cfg.block
+    projs = []
+    for p in cfg.projections:
+        m, n = p.d_in, p.d_out
+        d = {"m": m, "n": n, "name": p.name}
+        d["X"] = torch.randn((m, N), generator=g, device="cuda", dtype=torch.float32).to(dt)
+        d["dZ"] = torch.randn((n, N), generator=g, device="cuda", dtype=torch.float32).to(dt)
+        d["W"] = (torch.randn((n, m), generator=g, device="cuda", dtype=torch.float32) * cfg.sigma_w).to(dt)
+        for side, dim in (("R", m), ("P", n)):
+            nb = -(-dim // b)
+            d["theta_" + side] = torch.randn((nb, b * (b - 1) // 2), generator=g, device="cuda",
+                                             dtype=torch.float32) * cfg.sigma_theta
+            d["pi_" + side] = torch.randperm(dim, generator=g, device="cuda").to(torch.int32)
+            d["blk_" + side] = torch.empty((nb, b, b), device="cuda", dtype=dt)
+            d["dtheta_" + side] = torch.empty_like(d["theta_" + side])
+        projs.append(d)
+    return projs
+
+
+def cpu_baseline(cfg, n_tok):
+    """The fp64 oracle as it stands, timed on the host cores for a token sample of the
+    same layer; token-proportional and token-independent parts are timed apart and
+    recombined for the full token count."""
+    import numpy as np
+    from oracle import poetx_oracle as orc
+    from workloads import draw_projection
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    t_tok = t_cnp = 0.0
+    for pi_, p in enumerate(cfg.projections):
+        data = draw_projection(cfg, pi_, want=("W", "theta_R", "theta_P", "pi_R", "pi_P"))
+        rng = np.random.Generator(np.random.PCG64(7 + pi_))
+        X = rng.standard_normal((p.d_in, n_tok))
+        dZ = rng.standard_normal((p.d_out, n_tok))
+        b, k = cfg.block, cfg.neumann_k
+        t0 = time.perf_counter()
+        Q_R = orc.skew_from_packed(data["theta_R"], b, p.d_in)
+        Q_P = orc.skew_from_packed(data["theta_P"], b, p.d_out)
+        G_R, G_P = orc.cnp(Q_R, k), orc.cnp(Q_P, k)
+        t1 = time.perf_counter()
+        f = orc.linear_fwd(X, data["W"], data["pi_R"], data["pi_P"], G_R, G_P)
+        g = orc.linear_bwd(dZ, f, data["pi_R"], data["pi_P"], G_R, G_P)
+        t2 = time.perf_counter()
+        orc.packed_from_skew_grad(orc.cnp_bwd(Q_R, g["dG_R"], k), b, p.d_in)
+        orc.packed_from_skew_grad(orc.cnp_bwd(Q_P, g["dG_P"], k), b, p.d_out)
+        t3 = time.perf_counter()
+        t_cnp += (t1 - t0) + (t3 - t2)
+        t_tok += t2 - t1
+    full = t_cnp + t_tok * (cfg.n_tokens / n_tok)
+    return {"value": cfg.n_tokens / full, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"all 7 projections of {cfg.name}, {n_tok} of {cfg.n_tokens} tokens in fp64 numpy; "
+                      f"token-proportional part {t_tok:.2f}s scaled by {cfg.n_tokens // n_tok}, "
+                      f"series build/backward {t_cnp:.2f}s counted once"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 (no multi-GPU path exists)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2603_05500_amd as px
+    from workloads import get_config
+
+    px.load_library()
+    cfg = get_config(args.workload)
+    torch.cuda.set_device(0)
+    code = px.BF16 if cfg.dtype == "bf16" else px.F32
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    N, b, k = cfg.n_tokens, cfg.block, cfg.neumann_k
+    projs = make_inputs(cfg, torch)
+    nmax = max(p["n"] for p in projs)
+    mmax = max(p["m"] for p in projs)
+    Z = torch.empty((nmax, N), device="cuda", dtype=dt)
+    B = torch.empty((nmax, N), device="cuda", dtype=dt)
+    dX = torch.empty((mmax, N), device="cuda", dtype=dt)
+    dA = torch.empty((mmax, N), device="cuda", dtype=dt)
+    ws_bytes = cnp_bytes = 0
+    for p in projs:
+        p["desc"] = px.make_desc(p["m"], p["n"], b, k, N, code)
+        ws_bytes = max(ws_bytes, px.poetx_linear_workspace_bytes(p["desc"]))
+        cnp_bytes = max(cnp_bytes, px.poetx_cnp_workspace_bytes(max(p["m"], p["n"]), b))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    cws = torch.empty(cnp_bytes, dtype=torch.uint8, device="cuda")
+    prec = px.CNP_BF16 if code == px.BF16 else px.CNP_FP32
+
+    def step():
+        for p in projs:
+            m, n = p["m"], p["n"]
+            kw = {"E_bf16": p["blk_R"]} if code == px.BF16 else {"G_f32": p["blk_R"]}
+            px.poetx_cnp_build(p["theta_R"], m, b, k, prec, ws=cws, **kw)
+            kw = {"E_bf16": p["blk_P"]} if code == px.BF16 else {"G_f32": p["blk_P"]}
+            px.poetx_cnp_build(p["theta_P"], n, b, k, prec, ws=cws, **kw)
+            px.poetx_linear_fwd(p["desc"], p["X"], p["W"], p["pi_R"], p["pi_P"], p["blk_R"], p["blk_P"],
+                                Z[:n], B[:n], ws)
+            px.poetx_linear_bwd_input(p["desc"], p["dZ"], p["W"], p["pi_R"], p["pi_P"], p["blk_R"], p["blk_P"],
+                                      dX[:m], dA[:m], ws)
+            px.poetx_linear_bwd_skew(p["desc"], p["X"], p["dZ"], B[:n], dA[:m], p["pi_R"], p["pi_P"],
+                                     p["theta_R"], p["theta_P"], p["dtheta_R"], p["dtheta_P"], False, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    px.poetx_profile_begin(1 << 16)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms = e0.elapsed_time(e1) / args.steps
+    stages = px.poetx_profile_end()
+    assert all(torch.isfinite(p["dtheta_R"]).all() and torch.isfinite(p["dtheta_P"]).all() for p in projs)
+
+    dense_f, block_f, cnp_f = layer_flops(cfg)
+    dense_ms, dense_cnt = stages["dense"]
+    dense_tflops = dense_f * args.steps / (dense_ms * 1e-3) / 1e12 if dense_ms > 0 else 0.0
+    # HBM-bound block stages: algorithmic bytes = 2 s N d per apply (4 per projection side pair) ...
+    es = 2 if cfg.dtype == "bf16" else 4
+    apply_bytes = sum(4 * es * N * (p["m"] + p["n"]) for p in projs)      # 4 applies: read + write each
+    bgrad_bytes = sum(2 * es * N * (p["m"] + p["n"]) for p in projs)      # 2 reductions: two reads each
+    apply_ms, _ = stages["apply"]
+    bgrad_ms, _ = stages["blockgrad"]
+    out = {
+        "metric": "POET-X linear fwd+bwd tokens/sec at Llama-8B shapes; % MFMA peak",
+        "value": N / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: one decoder layer = 7 POET-X linears "
+                               f"({', '.join(f'{p.name} {p.d_out}x{p.d_in}' for p in cfg.projections)}), "
+                               f"N={N} tokens, b={b}, k={k}, fwd + bwd_input + bwd_skew + cnp_build",
+                   "tokens_per_step": N, "block": b, "neumann_k": k},
+        "mfma_peak_frac_layer": (dense_f + block_f + cnp_f) / (ms * 1e-3) / (PEAK_BF16_TFLOPS * 1e12),
+        "algorithmic_tflop_per_step": (dense_f + block_f + cnp_f) / 1e12,
+        "wall_ms_per_step": wall_ms / args.steps,
+        "stage_ms_per_step": {s: v[0] / args.steps for s, v in stages.items()},
+        "stage_rates": {
+            "dense_TFLOPs": dense_tflops,
+            "apply_GBs": apply_bytes * args.steps / (apply_ms * 1e-3) / 1e9 if apply_ms > 0 else 0.0,
+            "blockgrad_GBs": bgrad_bytes * args.steps / (bgrad_ms * 1e-3) / 1e9 if bgrad_ms > 0 else 0.0,
+        },
+        "roofline": {"bound": "mfma", "kernel": "dense bf16 product (B = W A, dA = W^T dB)",
+                     "achieved": dense_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": dense_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "launches": int(dense_cnt), "avg_launch_ms": dense_ms / max(int(dense_cnt), 1)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_tokens)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -91,6 +91,24 @@ int poetx_version(void);
  * matrix-core kernels, so that the two kernel families can be compared. */
 void poetx_debug_force_fma(int on);
 
+/* Stage timing for benchmarks (process-wide; off unless begun).  Between
+ * poetx_profile_begin and poetx_profile_end every group of kernels an entry
+ * point enqueues is bracketed by HIP events on the caller's stream (at most
+ * max_records groups; later ones are not timed).  poetx_profile_end waits for
+ * the recorded events and returns, per stage, the summed elapsed milliseconds
+ * and the number of timed groups; both arrays are HOST arrays of
+ * POETX_STAGE_COUNT entries. */
+typedef enum {
+  POETX_STAGE_CNP_FWD = 0,    /* skew + Cayley-Neumann series                    */
+  POETX_STAGE_APPLY = 1,      /* gather + block-diagonal product + scatter       */
+  POETX_STAGE_DENSE = 2,      /* B = W A and dA = W^T dB                         */
+  POETX_STAGE_BLOCKGRAD = 3,  /* per-block token reduction dG                    */
+  POETX_STAGE_CNP_BWD = 4,    /* series backward + packed projection             */
+  POETX_STAGE_COUNT = 5
+} poetx_stage;
+int poetx_profile_begin(int32_t max_records);
+int poetx_profile_end(double* ms_by_stage, int64_t* launches_by_stage);
+
 /* ---------------------------------------------------------------------------
  * skew_symmetric + cayley_neumann (Sec. 3.4, Eq. 8-9), batched over blocks:
  *   Q_j = skew(theta_j),  G_j = (I + Q_j)(I + Q_j + ... + Q_j^k)

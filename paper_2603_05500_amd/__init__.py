@@ -23,7 +23,9 @@ EXPORTS = (
     "poetx_cnp_workspace_bytes", "poetx_cnp_build",
     "poetx_perm_blockdiag_apply_left", "poetx_perm_blockdiag_apply_right", "poetx_perm_validate",
     "poetx_linear_workspace_bytes", "poetx_linear_fwd", "poetx_linear_bwd_input", "poetx_linear_bwd_skew",
+    "poetx_profile_begin", "poetx_profile_end",
 )
+STAGES = ("cnp_fwd", "apply", "dense", "blockgrad", "cnp_bwd")
 
 
 class LinearDesc(Structure):
@@ -79,6 +81,10 @@ def load_library(path: str | None = None):
     lib.poetx_linear_bwd_skew.restype = c_int
     lib.poetx_linear_bwd_skew.argtypes = [POINTER(LinearDesc)] + [c_void_p] * 10 + [c_int32, c_void_p, c_size_t,
                                                                                    c_void_p]
+    lib.poetx_profile_begin.restype = c_int
+    lib.poetx_profile_begin.argtypes = [c_int32]
+    lib.poetx_profile_end.restype = c_int
+    lib.poetx_profile_end.argtypes = [POINTER(ctypes.c_double), POINTER(c_int64)]
     _lib = lib
     return lib
 
@@ -194,3 +200,15 @@ def poetx_linear_bwd_skew(desc, X, dZ, saved_B, dA, perm_R, perm_P, theta_R, the
                                      _ptr(perm_P), _ptr(theta_R), _ptr(theta_P), _ptr(dtheta_R), _ptr(dtheta_P),
                                      int(bool(accumulate)), _ptr(ws), _ws_bytes(ws), _stream()),
            "poetx_linear_bwd_skew")
+
+
+def poetx_profile_begin(max_records: int = 65536):
+    _check(load_library().poetx_profile_begin(max_records), "poetx_profile_begin")
+
+
+def poetx_profile_end() -> dict:
+    """{stage: (milliseconds, timed launch groups)} since poetx_profile_begin."""
+    ms = (ctypes.c_double * len(STAGES))()
+    cnt = (c_int64 * len(STAGES))()
+    _check(load_library().poetx_profile_end(ms, cnt), "poetx_profile_end")
+    return {s: (ms[i], cnt[i]) for i, s in enumerate(STAGES)}

@@ -36,6 +36,7 @@ size_t cnp_bwd_ws_floats(int d, int b) { return (size_t)5 * ceil_div(d, b) * b *
 
 void apply_left_dispatch(int dtype, const void* V, void* out, int d, i64 cols, i64 ld, const int32_t* perm,
                          const void* blocks, int b, int trans, hipStream_t st) {
+  StageTimer tm(POETX_STAGE_APPLY, st);
   if (use_mfma(dtype) && mfma_apply_left_supported(d, cols, ld, b))
     mfma_apply_left(V, out, d, cols, ld, perm, blocks, b, trans, st);
   else
@@ -44,6 +45,7 @@ void apply_left_dispatch(int dtype, const void* V, void* out, int d, i64 cols, i
 
 void dense_dispatch(int dtype, int trans_w, const void* W, int n, int m, const void* act, void* out, i64 N,
                     hipStream_t st) {
+  StageTimer tm(POETX_STAGE_DENSE, st);
   if (use_mfma(dtype) && mfma_dense_supported(n, m, N)) mfma_dense(trans_w, W, n, m, act, out, N, st);
   else fma_dense(dtype, trans_w, W, n, m, act, out, N, st);
 }
@@ -87,6 +89,7 @@ int poetx_cnp_build(const float* theta, int32_t d, int32_t b, int32_t k, int32_t
   if (b > d) return POETX_ERR_BAD_SHAPE;
   if (!ws || ws_bytes < poetx_cnp_workspace_bytes(d, b)) return POETX_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
+  StageTimer tm(POETX_STAGE_CNP_FWD, st);
   if (precision == POETX_CNP_BF16 && !g_force_fma.load() && mfma_cnp_supported(b))
     mfma_cnp_build(theta, d, b, k, G_f32, E_bf16, (float*)ws, st);
   else
@@ -114,6 +117,7 @@ int poetx_perm_blockdiag_apply_right(const void* V, void* out, int64_t rows, int
   if (rows >= (1ll << 31)) return POETX_ERR_UNSUPPORTED;
   size_t bytes = (size_t)rows * ld * esize(dtype);
   if (overlap(V, bytes, out, bytes)) return POETX_ERR_INVALID_ARG;
+  StageTimer tm(POETX_STAGE_APPLY, (hipStream_t)stream);
   fma_apply_right(dtype, V, out, rows, d, ld, perm, blocks, b, transpose_G != 0, (hipStream_t)stream);
   return launch_status();
 }
@@ -200,10 +204,16 @@ int poetx_linear_bwd_skew(const poetx_linear_desc* desc, const void* X, const vo
     const int32_t* perm = side == 0 ? perm_P : perm_R;
     const float* theta = side == 0 ? theta_P : theta_R;
     float* dtheta = side == 0 ? dtheta_P : dtheta_R;
-    if (use_mfma(dt) && mfma_blockgrad_supported(d, N, b)) mfma_blockgrad(U, V, d, N, perm, b, dG, bg_ws, st);
-    else fma_blockgrad(dt, U, V, d, N, perm, b, dG, st);
-    if (fast_cnp) mfma_cnp_bwd(theta, dG, d, b, k, dtheta, accumulate != 0, chain, st);
-    else fma_cnp_bwd(theta, dG, d, b, k, dtheta, accumulate != 0, chain, st);
+    {
+      StageTimer tm(POETX_STAGE_BLOCKGRAD, st);
+      if (use_mfma(dt) && mfma_blockgrad_supported(d, N, b)) mfma_blockgrad(U, V, d, N, perm, b, dG, bg_ws, st);
+      else fma_blockgrad(dt, U, V, d, N, perm, b, dG, st);
+    }
+    {
+      StageTimer tm(POETX_STAGE_CNP_BWD, st);
+      if (fast_cnp) mfma_cnp_bwd(theta, dG, d, b, k, dtheta, accumulate != 0, chain, st);
+      else fma_cnp_bwd(theta, dG, d, b, k, dtheta, accumulate != 0, chain, st);
+    }
   }
   return launch_status();
 }

@@ -6,6 +6,16 @@
 
 namespace poetx {
 
+// Brackets the launches of one stage with HIP events when stage profiling is on.
+class StageTimer {
+ public:
+  StageTimer(int stage, hipStream_t st);
+  ~StageTimer();
+ private:
+  hipStream_t st_;
+  long idx_;
+};
+
 // ---- plain fp32-FMA path (fma_kernels.hip): any dtype, any block size ---------------
 // out = op(W) * act:  W is n x m row major.  trans_w == 0: out (n x N) = W act (m x N);
 // trans_w == 1: out (m x N) = W^T act (n x N).
