@@ -1,8 +1,6 @@
 // Placeholder: matrix-core kernels not built yet; everything reports unsupported.
 #include "poetx_kernels.h"
 namespace poetx {
-bool mfma_dense_supported(int, int, i64) { return false; }
-void mfma_dense(int, const void*, int, int, const void*, void*, i64, hipStream_t) {}
 bool mfma_apply_left_supported(int, i64, i64, int) { return false; }
 void mfma_apply_left(const void*, void*, int, i64, i64, const int32_t*, const void*, int, int, hipStream_t) {}
 bool mfma_blockgrad_supported(int, i64, int) { return false; }

@@ -198,3 +198,31 @@ def test_config2_fp32_storage_and_accumulate(lib):
     torch.cuda.synchronize()
     assert rel_err(to_np(dth_R) - 1.0, ref["dtheta_R"]) <= 1e-4
     assert rel_err(to_np(dth_P) - 1.0, ref["dtheta_P"]) <= 1e-4
+
+
+# ------------------------------------------------------------------ matrix-core shapes (multiples of 256)
+def synth_layer(seed, m, n, N, b, k, dtype, sigma_theta=0.01):
+    rng = RNG(seed)
+    rnd = round_f32 if dtype == "f32" else round_bf16
+    return {"m": m, "n": n, "N": N, "b": b, "k": k,
+            "X": rnd(rng.standard_normal((m, N))), "dZ": rnd(rng.standard_normal((n, N))),
+            "W": rnd(rng.standard_normal((n, m)) * 0.02),
+            "theta_R": draw_theta(rng, m, b, sigma_theta), "theta_P": draw_theta(rng, n, b, sigma_theta),
+            "pi_R": rng.permutation(m).astype(np.int32), "pi_P": rng.permutation(n).astype(np.int32)}
+
+
+@pytest.mark.parametrize("m,n,N,b,k", [(512, 256, 512, 64, 4), (256, 768, 256, 256, 5), (1024, 512, 768, 512, 3),
+                                       (768, 1024, 1280, 256, 4)])
+def test_bf16_layer_matrix_core_shapes(lib, m, n, N, b, k):
+    data = synth_layer(7000 + m + n + N + b, m, n, N, b, k, "bf16", 0.01 if b < 256 else 0.005)
+    ref = orc.linear_fwd_bwd_from_theta(data["X"], data["dZ"], data["W"], data["pi_R"], data["pi_P"],
+                                        data["theta_R"], data["theta_P"], b, k)
+    res = run_layer(data, "bf16")
+    check_layer(res, ref, data["pi_P"], "bf16")
+    # the plain-FMA kernels on the same inputs: both families must agree with the oracle
+    lib.poetx_debug_force_fma(True)
+    try:
+        res2 = run_layer(data, "bf16")
+    finally:
+        lib.poetx_debug_force_fma(False)
+    check_layer(res2, ref, data["pi_P"], "bf16")
