@@ -66,7 +66,8 @@ def make_inputs(cfg, torch):
             d["theta_" + side] = torch.randn((nb, b * (b - 1) // 2), generator=g, device="cuda",
                                              dtype=torch.float32) * cfg.sigma_theta
             d["pi_" + side] = torch.randperm(dim, generator=g, device="cuda").to(torch.int32)
-            d["blk_" + side] = torch.empty((nb, b, b), device="cuda", dtype=dt)
+            shape = (nb, 2, b, b) if cfg.dtype == "bf16" else (nb, b, b)  # bf16: (G - I, its transpose)
+            d["blk_" + side] = torch.empty(shape, device="cuda", dtype=dt)
             d["dtheta_" + side] = torch.empty_like(d["theta_" + side])
         projs.append(d)
     return projs

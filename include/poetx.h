@@ -27,9 +27,11 @@
  *    of the tail block with i >= r or j >= r are ignored on input and receive a
  *    zero gradient.
  *  - Block storage.  dtype POETX_F32: blocks are float G[nb][b][b].
- *    dtype POETX_BF16: blocks are bf16 E[nb][b][b] with E = G - I (the residual
- *    keeps the small part of G that rounding G itself to bf16 would lose); the
- *    kernels add the identity back in fp32.  poetx_cnp_build writes either.
+ *    dtype POETX_BF16: blocks are bf16 pairs E[nb][2][b][b]: E[j][0] = G_j - I
+ *    and E[j][1] = (G_j - I)^T.  The residual keeps the small part of G that
+ *    rounding G itself to bf16 would lose (the kernels add the identity back in
+ *    fp32); the stored transpose lets both op(G) = G and op(G) = G^T be read as
+ *    contiguous rows.  poetx_cnp_build writes either form.
  *  - bf16 buffers hold raw 16-bit patterns (uint16_t); accumulation is fp32.
  *  - All data pointers are DEVICE pointers unless marked host.  `stream` is a
  *    hipStream_t passed as void* (NULL = the null stream).  The caller owns
@@ -114,8 +116,8 @@ int poetx_profile_end(double* ms_by_stage, int64_t* launches_by_stage);
  *   Q_j = skew(theta_j),  G_j = (I + Q_j)(I + Q_j + ... + Q_j^k)
  *       = I + 2 sum_{p=1..k} Q_j^p + Q_j^{k+1}.
  * theta : [nb][b(b-1)/2] float, nb = ceil(d / b); d gives the ragged tail.
- * G_f32 : [nb][b][b] float, nullable.   E_bf16 : [nb][b][b] bf16 of G - I,
- * nullable (at least one must be given).
+ * G_f32 : [nb][b][b] float, nullable.   E_bf16 : [nb][2][b][b] bf16 pairs
+ * (G - I, its transpose), nullable (at least one must be given).
  * ws    : poetx_cnp_workspace_bytes(d, b) bytes.
  */
 size_t poetx_cnp_workspace_bytes(int32_t d, int32_t b);
@@ -157,7 +159,8 @@ int poetx_perm_validate(const int32_t* perm, int32_t d, int32_t* scratch, void* 
  */
 size_t poetx_linear_workspace_bytes(const poetx_linear_desc* desc);
 
-/* X: m x N.  W: n x m.  blocks_R / blocks_P: [ceil(m/b)][b][b], [ceil(n/b)][b][b].
+/* X: m x N.  W: n x m.  blocks_R / blocks_P: block storage of the dtype (see top)
+ * with ceil(m/b) and ceil(n/b) blocks.
  * Z: n x N (out).  saved_B: n x N (out; the one activation the fast variant
  * keeps for the backward pass, physical feature order). */
 int poetx_linear_fwd(const poetx_linear_desc* desc, const void* X, const void* W,

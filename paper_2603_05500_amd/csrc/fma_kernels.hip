@@ -102,30 +102,37 @@ struct StoreRowMajor {
   __device__ void operator()(int, int i, int j, float v) const { p[(i64)i * ld + j] = from_float<T>(v); }
 };
 
-// op(G_j)(i,l) for the structured apply; `residual` blocks hold G - I.
-template <class T, bool TRANS>
+// op(G_j)(i,l) for the structured apply.  RES = false: float G[nb][b][b].  RES = true: bf16
+// pairs [nb][2][b][b] holding G - I and its transpose; the identity is added back here.
+template <class T, bool TRANS, bool RES>
 struct BlockOpA {
-  const T* blocks; int b; int d; int residual;
-  static constexpr bool k_fast = !TRANS;
+  const T* blocks; int b; int d;
+  static constexpr bool k_fast = RES || !TRANS;
   __device__ float operator()(int j, int i, int l) const {
     int s = block_side(d, b, j);
     if (i >= s || l >= s) return 0.f;
-    i64 base = (i64)j * b * b;
-    float g = to_float(TRANS ? blocks[base + (i64)l * b + i] : blocks[base + (i64)i * b + l]);
-    return (residual && i == l) ? g + 1.f : g;
+    const i64 bb = (i64)b * b;
+    if (RES) {
+      float g = to_float(blocks[(i64)j * 2 * bb + (TRANS ? bb : 0) + (i64)i * b + l]);
+      return i == l ? g + 1.f : g;
+    }
+    return to_float(TRANS ? blocks[j * bb + (i64)l * b + i] : blocks[j * bb + (i64)i * b + l]);
   }
 };
 // op(G_j)(l,i) as the right-hand operand (apply_right).
-template <class T, bool TRANS>
+template <class T, bool TRANS, bool RES>
 struct BlockOpB {
-  const T* blocks; int b; int d; int residual;
-  static constexpr bool k_fast = TRANS;
+  const T* blocks; int b; int d;
+  static constexpr bool k_fast = !RES && TRANS;
   __device__ float operator()(int j, int l, int i) const {
     int s = block_side(d, b, j);
     if (i >= s || l >= s) return 0.f;
-    i64 base = (i64)j * b * b;
-    float g = to_float(TRANS ? blocks[base + (i64)i * b + l] : blocks[base + (i64)l * b + i]);
-    return (residual && i == l) ? g + 1.f : g;
+    const i64 bb = (i64)b * b;
+    if (RES) {
+      float g = to_float(blocks[(i64)j * 2 * bb + (TRANS ? bb : 0) + (i64)l * b + i]);
+      return i == l ? g + 1.f : g;
+    }
+    return to_float(TRANS ? blocks[j * bb + (i64)i * b + l] : blocks[j * bb + (i64)l * b + i]);
   }
 };
 template <class T>
@@ -207,7 +214,12 @@ struct StoreHorner {
   __device__ void operator()(int j, int i, int c, float v) const {
     i64 o = ((i64)j * b + i) * b + c;
     if (out) out[o] = (i == c) ? v + cdiag : v;
-    if (e) e[o] = float_to_bf16_bits((i == c) ? v + ediag : v);
+    if (e) {  // bf16 pair: value, then its transpose
+      const i64 bb = (i64)b * b;
+      const uint16_t r = float_to_bf16_bits((i == c) ? v + ediag : v);
+      e[(i64)j * 2 * bb + (i64)i * b + c] = r;
+      e[(i64)j * 2 * bb + bb + (i64)c * b + i] = r;
+    }
   }
 };
 // [A | Bm](i, kk) and [D ; T](kk, c) for the backward recursion step Bm <- A D + Bm T.
@@ -263,23 +275,23 @@ __global__ void perm_mark_kernel(const int32_t* perm, int d, int32_t* scratch) {
   if (atomicAdd(&scratch[p], 1) != 0) atomicAdd(&scratch[d], 1);
 }
 
-template <class T>
+template <class T, bool RES>
 void apply_left_t(const T* V, T* out, int d, i64 cols, i64 ld, const int32_t* perm, const T* blocks, int b,
-                  int trans, int residual, hipStream_t st) {
+                  int trans, hipStream_t st) {
   int nb = ceil_div(d, b);
   GatherRowsB<T> fb{V, ld, perm, b, d};
   ScatterRowsC<T> fc{out, ld, perm, b, d};
-  if (trans) launch_gemm(nb, b, cols, b, BlockOpA<T, true>{blocks, b, d, residual}, fb, fc, st);
-  else launch_gemm(nb, b, cols, b, BlockOpA<T, false>{blocks, b, d, residual}, fb, fc, st);
+  if (trans) launch_gemm(nb, b, cols, b, BlockOpA<T, true, RES>{blocks, b, d}, fb, fc, st);
+  else launch_gemm(nb, b, cols, b, BlockOpA<T, false, RES>{blocks, b, d}, fb, fc, st);
 }
-template <class T>
+template <class T, bool RES>
 void apply_right_t(const T* V, T* out, i64 rows, int d, i64 ld, const int32_t* perm, const T* blocks, int b,
-                   int trans, int residual, hipStream_t st) {
+                   int trans, hipStream_t st) {
   int nb = ceil_div(d, b);
   GatherColsA<T> fa{V, ld, perm, b, d};
   ScatterColsC<T> fc{out, ld, perm, b, d};
-  if (trans) launch_gemm(nb, rows, b, b, fa, BlockOpB<T, true>{blocks, b, d, residual}, fc, st);
-  else launch_gemm(nb, rows, b, b, fa, BlockOpB<T, false>{blocks, b, d, residual}, fc, st);
+  if (trans) launch_gemm(nb, rows, b, b, fa, BlockOpB<T, true, RES>{blocks, b, d}, fc, st);
+  else launch_gemm(nb, rows, b, b, fa, BlockOpB<T, false, RES>{blocks, b, d}, fc, st);
 }
 template <class T>
 void dense_t(int trans_w, const T* W, int n, int m, const T* act, T* out, i64 N, hipStream_t st) {
@@ -300,17 +312,17 @@ void fma_dense(int dtype, int trans_w, const void* W, int n, int m, const void* 
 void fma_apply_left(int dtype, const void* V, void* out, int d, i64 cols, i64 ld, const int32_t* perm,
                     const void* blocks, int b, int transpose_G, hipStream_t st) {
   if (dtype == POETX_F32)
-    apply_left_t<float>((const float*)V, (float*)out, d, cols, ld, perm, (const float*)blocks, b, transpose_G, 0, st);
+    apply_left_t<float, false>((const float*)V, (float*)out, d, cols, ld, perm, (const float*)blocks, b, transpose_G, st);
   else
-    apply_left_t<bf16_t>((const bf16_t*)V, (bf16_t*)out, d, cols, ld, perm, (const bf16_t*)blocks, b, transpose_G, 1, st);
+    apply_left_t<bf16_t, true>((const bf16_t*)V, (bf16_t*)out, d, cols, ld, perm, (const bf16_t*)blocks, b, transpose_G, st);
 }
 
 void fma_apply_right(int dtype, const void* V, void* out, i64 rows, int d, i64 ld, const int32_t* perm,
                      const void* blocks, int b, int transpose_G, hipStream_t st) {
   if (dtype == POETX_F32)
-    apply_right_t<float>((const float*)V, (float*)out, rows, d, ld, perm, (const float*)blocks, b, transpose_G, 0, st);
+    apply_right_t<float, false>((const float*)V, (float*)out, rows, d, ld, perm, (const float*)blocks, b, transpose_G, st);
   else
-    apply_right_t<bf16_t>((const bf16_t*)V, (bf16_t*)out, rows, d, ld, perm, (const bf16_t*)blocks, b, transpose_G, 1, st);
+    apply_right_t<bf16_t, true>((const bf16_t*)V, (bf16_t*)out, rows, d, ld, perm, (const bf16_t*)blocks, b, transpose_G, st);
 }
 
 void fma_blockgrad(int dtype, const void* U, const void* V, int d, i64 N, const int32_t* perm, int b, float* dG,
@@ -380,7 +392,13 @@ void fma_cnp_bwd(const float* theta, const float* dG, int d, int b, int k, float
       ca = 1 - ca;
     }
   }
-  hipLaunchKernelGGL(skew_project_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, bcur, b, d, nb, dtheta,
+  skew_project_launch(bcur, b, d, dtheta, accumulate, st);
+}
+
+void skew_project_launch(const float* M, int b, int d, float* dtheta, int accumulate, hipStream_t st) {
+  const int nb = ceil_div(d, b);
+  const i64 total = (i64)nb * b * b;
+  hipLaunchKernelGGL(skew_project_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, M, b, d, nb, dtheta,
                      accumulate);
 }
 

@@ -1,0 +1,179 @@
+// Cayley-Neumann series and its backward on the matrix cores (Sec. 3.4, Eq. 8-9),
+// batched over the blocks of one side, for block sides that are multiples of 256.
+//
+// Every b x b product runs as bf16 x bf16 -> fp32 on the batched tile kernel.  To
+// keep the small terms, the chain is carried in residual form: with H = 2I + H'
+// Horner's rule H <- H Q + 2I becomes H' <- 2Q + H' Q, where only the small
+// product H' Q goes through bf16 and the 2Q term is added in fp32 from theta.
+// After k steps H' is G - I.  The backward recursion (see fma_cnp_bwd) is carried
+// the same way: A = 2I + A', A' <- 2T + A' T and Bm <- 2D + A' D + Bm T with
+// T = -Q, the 2D term added in fp32.
+#include "mfma_gemm.h"
+
+namespace poetx {
+void skew_project_launch(const float* M, int b, int d, float* dtheta, int accumulate, hipStream_t st);
+
+namespace {
+
+constexpr int CBM = 256, CBN = 256, CBK = 64;
+
+__device__ inline float skew_at(const float* th, int i, int c, int b) {
+  if (i == c) return 0.f;
+  return i < c ? th[packed_index(i, c, b)] : -th[packed_index(c, i, b)];
+}
+
+// Qb = bf16(Q), Tb = bf16(-Q) for every block.
+__global__ void skew_materialize_kernel(const float* __restrict__ theta, int b, i64 total, uint16_t* __restrict__ Qb,
+                                        uint16_t* __restrict__ Tb) {
+  i64 idx = (i64)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  int c = (int)(idx % b);
+  int i = (int)((idx / b) % b);
+  i64 j = idx / ((i64)b * b);
+  float q = skew_at(theta + j * ((i64)b * (b - 1) / 2), i, c, b);
+  if (Qb) Qb[idx] = float_to_bf16_bits(q);
+  if (Tb) Tb[idx] = float_to_bf16_bits(-q);
+}
+
+__global__ void to_bf16_kernel(const float4* __restrict__ in, uint2* __restrict__ out, i64 n4) {
+  i64 idx = (i64)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n4) return;
+  float4 v = in[idx];
+  uint2 o;
+  o.x = mm::pack2_bf16(v.x, v.y);
+  o.y = mm::pack2_bf16(v.z, v.w);
+  out[idx] = o;
+}
+
+// value = acc + 2 * sign * skew(theta)(row, col).  Writes whichever outputs are set:
+// Hn (bf16 chain value), G (fp32, + I), E (bf16 pair [nb][2][b][b]: value and its transpose).
+struct EpiHorner {
+  const float* theta;
+  float sign;
+  int b;
+  uint16_t* Hn;
+  float* G;
+  uint16_t* E;
+  __device__ void operator()(int j, int, int row, int col, float4 a) const {
+    const float* th = theta + (i64)j * ((i64)b * (b - 1) / 2);
+    float v[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] += 2.f * sign * skew_at(th, row, col + e, b);
+    const i64 o = ((i64)j * b + row) * b + col;
+    uint2 pk;
+    pk.x = mm::pack2_bf16(v[0], v[1]);
+    pk.y = mm::pack2_bf16(v[2], v[3]);
+    if (Hn) *reinterpret_cast<uint2*>(Hn + o) = pk;
+    if (G) {
+      float4 gv = make_float4(v[0], v[1], v[2], v[3]);
+      gv.x += (row == col) ? 1.f : 0.f;
+      gv.y += (row == col + 1) ? 1.f : 0.f;
+      gv.z += (row == col + 2) ? 1.f : 0.f;
+      gv.w += (row == col + 3) ? 1.f : 0.f;
+      *reinterpret_cast<float4*>(G + o) = gv;
+    }
+    if (E) {
+      const i64 base = (i64)j * 2 * b * b;
+      *reinterpret_cast<uint2*>(E + base + (i64)row * b + col) = pk;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) E[base + (i64)b * b + (i64)(col + e) * b + row] = float_to_bf16_bits(v[e]);
+    }
+  }
+};
+
+// value = acc + 2 * D(row, col): next chain value in bf16 and/or the final fp32 result.
+struct EpiBwd {
+  const float* D;
+  int b;
+  uint16_t* Bn;
+  float* Bf;
+  __device__ void operator()(int j, int, int row, int col, float4 a) const {
+    const i64 o = ((i64)j * b + row) * b + col;
+    float4 d = *reinterpret_cast<const float4*>(D + o);
+    float4 v = make_float4(a.x + 2.f * d.x, a.y + 2.f * d.y, a.z + 2.f * d.z, a.w + 2.f * d.w);
+    if (Bn) {
+      uint2 pk;
+      pk.x = mm::pack2_bf16(v.x, v.y);
+      pk.y = mm::pack2_bf16(v.z, v.w);
+      *reinterpret_cast<uint2*>(Bn + o) = pk;
+    }
+    if (Bf) *reinterpret_cast<float4*>(Bf + o) = v;
+  }
+};
+
+mm::Args batched_args(int b) {
+  mm::Args g{};
+  g.tiles_m = b / CBM;
+  g.tiles_n = b / CBN;
+  return g;
+}
+void set_src(mm::Source& s, const uint16_t* A, const uint16_t* B, int b) {
+  s.A = A; s.B = B; s.lda = b; s.ldb = b; s.sA = (i64)b * b; s.sB = (i64)b * b; s.ktiles = b / CBK;
+}
+
+}  // namespace
+
+bool mfma_cnp_supported(int d, int b) { return (b == 256 || b == 512) && d % b == 0; }
+
+// ws: Qb | H0 | H1, bf16 nb*b*b each.
+void mfma_cnp_build(const float* theta, int d, int b, int k, float* G_f32, void* E_bf16, float* ws, hipStream_t st) {
+  const int nb = d / b;
+  const i64 total = (i64)nb * b * b;
+  uint16_t* Qb = (uint16_t*)ws;
+  uint16_t* H[2] = {Qb + total, Qb + 2 * total};
+  hipLaunchKernelGGL(skew_materialize_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, theta, b, total, Qb,
+                     (uint16_t*)nullptr);
+  const uint16_t* cur = Qb;  // H'_1 = Q
+  for (int step = 0; step < k; ++step) {
+    const bool last = step == k - 1;
+    mm::Args g = batched_args(b);
+    g.nsrc = 1;
+    set_src(g.s[0], cur, Qb, b);
+    uint16_t* nxt = H[step & 1];
+    EpiHorner epi{theta, 1.f, b, last ? nullptr : nxt, last ? G_f32 : nullptr, last ? (uint16_t*)E_bf16 : nullptr};
+    mm::launch<CBM, CBN, CBK, true, false, false>(g, epi, nb, 1, st);
+    cur = nxt;
+  }
+}
+
+// ws: Tb | Db | A0 | A1 | B0 | B1 (bf16 nb*b*b each) | Bfinal (fp32 nb*b*b)  = 4 floats per element.
+void mfma_cnp_bwd(const float* theta, const float* dG, int d, int b, int k, float* dtheta, int accumulate, float* ws,
+                  hipStream_t st) {
+  const int nb = d / b;
+  const i64 total = (i64)nb * b * b;
+  uint16_t* Tb = (uint16_t*)ws;
+  uint16_t* Db = Tb + total;
+  uint16_t* A[2] = {Tb + 2 * total, Tb + 3 * total};
+  uint16_t* Bb[2] = {Tb + 4 * total, Tb + 5 * total};
+  float* Bfinal = (float*)(Tb + 6 * total);
+  hipLaunchKernelGGL(skew_materialize_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, theta, b, total,
+                     (uint16_t*)nullptr, Tb);
+  hipLaunchKernelGGL(to_bf16_kernel, dim3(ceil_div(total / 4, 256)), dim3(256), 0, st, (const float4*)dG, (uint2*)Db,
+                     total / 4);
+  const uint16_t* acur = Tb;  // A'_1 = T
+  const uint16_t* bcur = Db;  // Bm_1 = D
+  int ia = 0, ib = 0;
+  for (int p = k - 1; p >= 0; --p) {
+    const bool last = p == 0;
+    mm::Args g = batched_args(b);
+    g.nsrc = 2;
+    set_src(g.s[0], acur, Db, b);  // A' D
+    set_src(g.s[1], bcur, Tb, b);  // Bm T
+    EpiBwd epi{dG, b, last ? nullptr : Bb[ib], last ? Bfinal : nullptr};
+    mm::launch<CBM, CBN, CBK, true, false, false>(g, epi, nb, 1, st);
+    if (!last) {
+      mm::Args h = batched_args(b);
+      h.nsrc = 1;
+      set_src(h.s[0], acur, Tb, b);  // A' T
+      EpiHorner eh{theta, -1.f, b, A[ia], nullptr, nullptr};
+      mm::launch<CBM, CBN, CBK, true, false, false>(h, eh, nb, 1, st);
+      acur = A[ia];
+      ia ^= 1;
+      bcur = Bb[ib];
+      ib ^= 1;
+    }
+  }
+  skew_project_launch(Bfinal, b, d, dtheta, accumulate, st);
+}
+
+}  // namespace poetx

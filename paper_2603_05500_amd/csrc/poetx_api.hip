@@ -32,6 +32,7 @@ int check_desc(const poetx_linear_desc* d) {
   return POETX_OK;
 }
 
+// dG plus four chain buffers of nb*b*b floats
 size_t cnp_bwd_ws_floats(int d, int b) { return (size_t)5 * ceil_div(d, b) * b * b; }
 
 void apply_left_dispatch(int dtype, const void* V, void* out, int d, i64 cols, i64 ld, const int32_t* perm,
@@ -90,7 +91,7 @@ int poetx_cnp_build(const float* theta, int32_t d, int32_t b, int32_t k, int32_t
   if (!ws || ws_bytes < poetx_cnp_workspace_bytes(d, b)) return POETX_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   StageTimer tm(POETX_STAGE_CNP_FWD, st);
-  if (precision == POETX_CNP_BF16 && !g_force_fma.load() && mfma_cnp_supported(b))
+  if (precision == POETX_CNP_BF16 && !g_force_fma.load() && mfma_cnp_supported(d, b))
     mfma_cnp_build(theta, d, b, k, G_f32, E_bf16, (float*)ws, st);
   else
     fma_cnp_build(theta, d, b, k, G_f32, E_bf16, (float*)ws, st);
@@ -196,7 +197,6 @@ int poetx_linear_bwd_skew(const poetx_linear_desc* desc, const void* X, const vo
   float* dG = (float*)ws;
   float* chain = dG + (size_t)ceil_div(dmax, b) * b * b;
   void* bg_ws = (char*)ws + align256(cnp_bwd_ws_floats(dmax, b) * sizeof(float));
-  const bool fast_cnp = desc->cnp_precision == POETX_CNP_BF16 && !g_force_fma.load() && mfma_cnp_supported(b);
   for (int side = 0; side < 2; ++side) {
     const void* U = side == 0 ? saved_B : X;   // mm3 backward: dG_P = B' dZ'^T; mm1 backward: dG_R = X' dA'^T
     const void* V = side == 0 ? dZ : dA;
@@ -204,6 +204,7 @@ int poetx_linear_bwd_skew(const poetx_linear_desc* desc, const void* X, const vo
     const int32_t* perm = side == 0 ? perm_P : perm_R;
     const float* theta = side == 0 ? theta_P : theta_R;
     float* dtheta = side == 0 ? dtheta_P : dtheta_R;
+    const bool fast_cnp = desc->cnp_precision == POETX_CNP_BF16 && !g_force_fma.load() && mfma_cnp_supported(d, b);
     {
       StageTimer tm(POETX_STAGE_BLOCKGRAD, st);
       if (use_mfma(dt) && mfma_blockgrad_supported(d, N, b)) mfma_blockgrad(U, V, d, N, perm, b, dG, bg_ws, st);

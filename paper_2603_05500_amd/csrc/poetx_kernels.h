@@ -35,6 +35,9 @@ void fma_cnp_build(const float* theta, int d, int b, int k, float* G_f32, void* 
 void fma_cnp_bwd(const float* theta, const float* dG, int d, int b, int k, float* dtheta, int accumulate,
                  float* ws, hipStream_t st);
 
+// dtheta[j][idx(i,c)] (+)= M[j][i][c] - M[j][c][i] (Sec. 3.4: gradient on the packed parameters).
+void skew_project_launch(const float* M, int b, int d, float* dtheta, int accumulate, hipStream_t st);
+
 void perm_validate_launch(const int32_t* perm, int d, int32_t* scratch, hipStream_t st);
 
 // ---- matrix-core path for bf16 (mfma_*.hip) -------------------------------------------
@@ -48,7 +51,7 @@ bool mfma_blockgrad_supported(int d, i64 N, int b);
 size_t mfma_blockgrad_workspace_bytes(int d, i64 N, int b);
 void mfma_blockgrad(const void* U, const void* V, int d, i64 N, const int32_t* perm, int b, float* dG,
                     void* ws, hipStream_t st);
-bool mfma_cnp_supported(int b);
+bool mfma_cnp_supported(int d, int b);
 void mfma_cnp_build(const float* theta, int d, int b, int k, float* G_f32, void* E_bf16, float* ws,
                     hipStream_t st);
 void mfma_cnp_bwd(const float* theta, const float* dG, int d, int b, int k, float* dtheta, int accumulate,

@@ -47,7 +47,7 @@ def build_blocks(theta: np.ndarray, d: int, b: int, k: int, dtype_name: str, pre
         px.poetx_cnp_build(th, d, b, k, precision, G_f32=G, E_bf16=None, ws=ws)
         torch.cuda.synchronize()
         return G, to_np(G)
-    E = torch.empty((nb, b, b), dtype=torch.bfloat16, device="cuda")
+    E = torch.empty((nb, 2, b, b), dtype=torch.bfloat16, device="cuda")
     px.poetx_cnp_build(th, d, b, k, precision, G_f32=G, E_bf16=E, ws=ws)
     torch.cuda.synchronize()
     return E, to_np(G)

@@ -18,6 +18,11 @@ def draw_theta(rng, d, b, sigma):
     return round_f32(rng.standard_normal((nb, b * (b - 1) // 2)) * sigma)
 
 
+def pair(E):
+    """bf16 block storage: (E, E^T) per block."""
+    return np.stack([E, np.swapaxes(E, 1, 2)], axis=1)
+
+
 # ------------------------------------------------------------------ cnp_build
 @pytest.mark.parametrize("d,b,k", [(64, 32, 3), (256, 32, 4), (96, 64, 4), (1376, 64, 4), (512, 256, 5),
                                    (1024, 512, 5), (40, 8, 1), (48, 16, 2)])
@@ -28,7 +33,7 @@ def test_cnp_build(lib, d, b, k, precision):
     th = to_dev(theta, torch.float32)
     nb = theta.shape[0]
     G = torch.empty((nb, b, b), dtype=torch.float32, device="cuda")
-    E = torch.empty((nb, b, b), dtype=torch.bfloat16, device="cuda")
+    E = torch.empty((nb, 2, b, b), dtype=torch.bfloat16, device="cuda")
     ws = ws_tensor(lib.poetx_cnp_workspace_bytes(d, b))
     lib.poetx_cnp_build(th, d, b, k, lib.CNP_FP32 if precision == "fp32" else lib.CNP_BF16, G, E, ws)
     torch.cuda.synchronize()
@@ -38,7 +43,8 @@ def test_cnp_build(lib, d, b, k, precision):
     eye = np.eye(b)
     # the residual must keep the small part of G: compare G - I on its own scale
     assert rel_err(to_np(G) - eye, ref - eye) <= tol
-    assert rel_err(to_np(E), ref - eye) <= 2e-2
+    assert rel_err(to_np(E)[:, 0], ref - eye) <= 2e-2
+    assert torch.equal(E[:, 1], E[:, 0].transpose(1, 2))  # stored transpose, bit for bit
     r = orc.tail_side(d, b)
     if r < b:  # identity padding of the ragged tail block, exactly
         Gt = to_np(G)[-1]
@@ -64,7 +70,7 @@ def test_apply_left(lib, d, b, cols, dtype, transpose):
     out = torch.empty_like(Vd)
     lib.poetx_perm_blockdiag_apply_left(Vd, out, torch.from_numpy(pi).cuda(), blocks, b, transpose)
     torch.cuda.synchronize()
-    G_used = G if dtype == "f32" else to_np(blocks) + np.eye(b)  # the blocks the kernel was given
+    G_used = G if dtype == "f32" else to_np(blocks)[:, 0] + np.eye(b)  # the blocks the kernel was given
     ref = orc.apply_left(V, pi, G_used, transpose)
     assert rel_err(to_np(out), ref) <= TOL[dtype]
     ref_exactG = orc.apply_left(V, pi, orc.cnp(orc.skew_from_packed(theta, b, d), 4), transpose)
@@ -106,7 +112,7 @@ def test_apply_indexing_bit_exact(lib, d, b, cols, dtype):
         G[j, np.arange(s, b), np.arange(s, b)] = 1.0
     V = rng.integers(-64, 65, size=(d, cols)).astype(np.float64)
     pi = rng.permutation(d).astype(np.int32)
-    blocks = to_dev(G if dtype == "f32" else G - np.eye(b), tdtype(dtype))
+    blocks = to_dev(G if dtype == "f32" else pair(G - np.eye(b)), tdtype(dtype))
     Vd = to_dev(V, tdtype(dtype))
     for transpose in (False, True):
         out = torch.empty_like(Vd)
@@ -115,7 +121,7 @@ def test_apply_indexing_bit_exact(lib, d, b, cols, dtype):
         assert np.array_equal(to_np(out), orc.apply_left(V, pi, G, transpose))
     # identity blocks: gather followed by scatter is the identity map, bit for bit
     eye = np.broadcast_to(np.eye(b), (nb, b, b)).copy()
-    blocks = to_dev(eye if dtype == "f32" else eye * 0, tdtype(dtype))
+    blocks = to_dev(eye if dtype == "f32" else pair(eye * 0), tdtype(dtype))
     Vr = to_dev((round_f32 if dtype == "f32" else round_bf16)(rng.standard_normal((d, cols))), tdtype(dtype))
     out = torch.empty_like(Vr)
     lib.poetx_perm_blockdiag_apply_left(Vr, out, torch.from_numpy(pi).cuda(), blocks, b, True)
