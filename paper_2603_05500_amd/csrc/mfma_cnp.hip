@@ -15,7 +15,8 @@ void skew_project_launch(const float* M, int b, int d, float* dtheta, int accumu
 
 namespace {
 
-constexpr int CBM = 256, CBN = 256, CBK = 64;
+// Small output tiles: one side has only a few blocks, so 64 x 64 tiles are what fills the 256 CUs.
+constexpr int CBM = 64, CBN = 64, CBK = 64;
 
 __device__ inline float skew_at(const float* th, int i, int c, int b) {
   if (i == c) return 0.f;

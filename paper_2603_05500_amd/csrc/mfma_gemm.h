@@ -27,6 +27,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef short short8v __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) short4v* lds_s4p;
 
 // Row pad of [k][x] tiles: 32 elements (64 B) spreads the four k rows one
@@ -115,7 +116,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(Args g, Epi epi) {
   const int wm = wave >> 1, wn = wave & 1;
   const int i0 = tile_m * BM, j0 = tile_n * BN;
 
-  uint4 ra[C::A_CHUNKS], rb[C::B_CHUNKS];
+  u32x4 ra[C::A_CHUNKS], rb[C::B_CHUNKS];
   // Gathered rows: element offsets of this thread's rows, fixed over the k loop.
   i64 ga[GATHER ? C::A_CHUNKS : 1], gb[GATHER ? C::B_CHUNKS : 1];
   if (GATHER) {
@@ -136,10 +137,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(Args g, Epi epi) {
       if (A_KMAJOR) {
         const int row = c / (BK / 8), ch = c % (BK / 8);
         const i64 off = GATHER ? ga[s] : (i64)(i0 + row) * src.lda;
-        ra[s] = *reinterpret_cast<const uint4*>(Ab + off + k0 + ch * 8);
+        ra[s] = *reinterpret_cast<const u32x4*>(Ab + off + k0 + ch * 8);
       } else {
         const int row = c / (BM / 8), ch = c % (BM / 8);
-        ra[s] = *reinterpret_cast<const uint4*>(Ab + (k0 + row) * src.lda + i0 + ch * 8);
+        ra[s] = *reinterpret_cast<const u32x4*>(Ab + (k0 + row) * src.lda + i0 + ch * 8);
       }
     }
 #pragma unroll
@@ -148,10 +149,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(Args g, Epi epi) {
       if (B_KMAJOR) {
         const int row = c / (BK / 8), ch = c % (BK / 8);
         const i64 off = GATHER ? gb[s] : (i64)(j0 + row) * src.ldb;
-        rb[s] = *reinterpret_cast<const uint4*>(Bb + off + k0 + ch * 8);
+        rb[s] = *reinterpret_cast<const u32x4*>(Bb + off + k0 + ch * 8);
       } else {
         const int row = c / (BN / 8), ch = c % (BN / 8);
-        rb[s] = *reinterpret_cast<const uint4*>(Bb + (k0 + row) * src.ldb + j0 + ch * 8);
+        rb[s] = *reinterpret_cast<const u32x4*>(Bb + (k0 + row) * src.ldb + j0 + ch * 8);
       }
     }
   };
@@ -163,14 +164,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(Args g, Epi epi) {
       const int c = tid + s * 256;
       const int row = A_KMAJOR ? c / (BK / 8) : c / (BM / 8);
       const int ch = A_KMAJOR ? c % (BK / 8) : c % (BM / 8);
-      *reinterpret_cast<uint4*>(As + row * C::SA + ch * 8) = ra[s];
+      *reinterpret_cast<u32x4*>(As + row * C::SA + ch * 8) = ra[s];
     }
 #pragma unroll
     for (int s = 0; s < C::B_CHUNKS; ++s) {
       const int c = tid + s * 256;
       const int row = B_KMAJOR ? c / (BK / 8) : c / (BN / 8);
       const int ch = B_KMAJOR ? c % (BK / 8) : c % (BN / 8);
-      *reinterpret_cast<uint4*>(Bs + row * C::SB + ch * 8) = rb[s];
+      *reinterpret_cast<u32x4*>(Bs + row * C::SB + ch * 8) = rb[s];
     }
   };
 
@@ -191,13 +192,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(Args g, Epi epi) {
     else load_global(g.s[1], kt - kt0);
   };
 
-  fetch(0);
-  store_lds(0);
-  __syncthreads();
-  for (int kt = 0; kt < KT; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < KT) fetch(kt + 1);
-    const uint16_t* As = lds + cur * C::STAGE;
+  auto multiply = [&](int stage) {
+    const uint16_t* As = lds + stage * C::STAGE;
     const uint16_t* Bs = As + C::A_ELEMS;
 #pragma unroll 2
     for (int ks = 0; ks < BK / 16; ++ks) {
@@ -218,9 +214,21 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(Args g, Epi epi) {
         for (int c = 0; c < TN; ++c)
           acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c], fa[a], acc[a][c], 0, 0, 0);
     }
-    if (kt + 1 < KT) store_lds(cur ^ 1);
+  };
+
+  // The last tile is peeled so that the loads inside the loop are unconditional: the
+  // staging registers then have a single definition per iteration and nothing has to
+  // wait for them before the multiply.
+  fetch(0);
+  store_lds(0);
+  __syncthreads();
+  for (int kt = 0; kt + 1 < KT; ++kt) {
+    fetch(kt + 1);
+    multiply(kt & 1);
+    store_lds((kt & 1) ^ 1);
     __syncthreads();
   }
+  multiply((KT - 1) & 1);
 
   const int h = lane >> 5, li = lane & 31;
 #pragma unroll
