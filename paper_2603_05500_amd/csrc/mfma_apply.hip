@@ -22,6 +22,23 @@ namespace {
 
 using mm::bf16x8;
 using mm::floatx16;
+using mm::short4v;
+using mm::short8v;
+
+// Row pad of the gathered [l][token] tile: 32 elements (64 B) spreads the four l rows one
+// transposing read touches over different bank groups.
+constexpr int PAD_T = 32;
+
+// 32 x 16 matrix-core operand fragment from a padded [k][x] LDS tile (row stride `stride`
+// elements): lane gets column x0 + lane%32 and contraction elements k0 + 8*(lane/32) + 0..7.
+__device__ inline bf16x8 frag_from_kx(const uint16_t* tile, int stride, int k0, int x0, int lane) {
+  const int q = lane >> 4, i = lane & 15;
+  const uint16_t* p = tile + (k0 + 8 * (q >> 1) + (i >> 2)) * stride + x0 + 16 * (q & 1) + 4 * (i & 3);
+  short4v lo = mm::lds_read_tr((const char*)p);
+  short4v hi = mm::lds_read_tr((const char*)(p + 4 * stride));
+  short8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, v);
+}
 
 // B: block side.  BN: tokens per workgroup.  4 waves, wave w owns output rows
 // [w*B/4, (w+1)*B/4) for all BN tokens.
@@ -29,7 +46,7 @@ template <int B, int BN>
 __global__ __launch_bounds__(256) void apply_left_bf16_kernel(const uint16_t* __restrict__ V, uint16_t* __restrict__ out,
                                                                i64 ld, const int32_t* __restrict__ perm,
                                                                const uint16_t* __restrict__ blocks, int trans) {
-  constexpr int SX = BN + mm::PAD_T;
+  constexpr int SX = BN + PAD_T;
   constexpr int TM = B / 4 / 32, TN = BN / 32;
   constexpr int CPR = BN / 8;                 // 16-byte chunks per row
   constexpr int CHUNKS = B * CPR / 256;       // per thread
@@ -74,7 +91,7 @@ __global__ __launch_bounds__(256) void apply_left_bf16_kernel(const uint16_t* __
     }
     bf16x8 fb[TN];
 #pragma unroll
-    for (int c = 0; c < TN; ++c) fb[c] = mm::frag_from_kx(xs, SX, ks * 16, c * 32, lane);
+    for (int c = 0; c < TN; ++c) fb[c] = frag_from_kx(xs, SX, ks * 16, c * 32, lane);
 #pragma unroll
     for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -115,7 +132,7 @@ __global__ __launch_bounds__(256) void apply_left_bf16_kernel(const uint16_t* __
 template <int B, int BN>
 void launch_apply(const uint16_t* V, uint16_t* out, int d, i64 cols, i64 ld, const int32_t* perm, const uint16_t* E,
                   int trans, hipStream_t st) {
-  constexpr size_t LDS = (size_t)B * (BN + mm::PAD_T) * sizeof(uint16_t);
+  constexpr size_t LDS = (size_t)B * (BN + PAD_T) * sizeof(uint16_t);
   auto kern = apply_left_bf16_kernel<B, BN>;
   static bool configured = false;
   if (!configured) {

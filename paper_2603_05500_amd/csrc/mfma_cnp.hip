@@ -132,7 +132,7 @@ void mfma_cnp_build(const float* theta, int d, int b, int k, float* G_f32, void*
     set_src(g.s[0], cur, Qb, b);
     uint16_t* nxt = H[step & 1];
     EpiHorner epi{theta, 1.f, b, last ? nullptr : nxt, last ? G_f32 : nullptr, last ? (uint16_t*)E_bf16 : nullptr};
-    mm::launch<CBM, CBN, CBK, true, false, false>(g, epi, nb, 1, st);
+    mm::launch<CBM, CBN, 2, 2, true, false, false>(g, epi, nb, 1, st);
     cur = nxt;
   }
 }
@@ -161,13 +161,13 @@ void mfma_cnp_bwd(const float* theta, const float* dG, int d, int b, int k, floa
     set_src(g.s[0], acur, Db, b);  // A' D
     set_src(g.s[1], bcur, Tb, b);  // Bm T
     EpiBwd epi{dG, b, last ? nullptr : Bb[ib], last ? Bfinal : nullptr};
-    mm::launch<CBM, CBN, CBK, true, false, false>(g, epi, nb, 1, st);
+    mm::launch<CBM, CBN, 2, 2, true, false, false>(g, epi, nb, 1, st);
     if (!last) {
       mm::Args h = batched_args(b);
       h.nsrc = 1;
       set_src(h.s[0], acur, Tb, b);  // A' T
       EpiHorner eh{theta, -1.f, b, A[ia], nullptr, nullptr};
-      mm::launch<CBM, CBN, CBK, true, false, false>(h, eh, nb, 1, st);
+      mm::launch<CBM, CBN, 2, 2, true, false, false>(h, eh, nb, 1, st);
       acur = A[ia];
       ia ^= 1;
       bcur = Bb[ib];

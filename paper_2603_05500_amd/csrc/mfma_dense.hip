@@ -27,11 +27,11 @@ void mfma_dense(int trans_w, const void* W, int n, int m, const void* act, void*
   if (!trans_w) {
     g.tiles_m = n / DBM;
     g.s[0].ktiles = m / DBK;
-    mm::launch<DBM, DBN, DBK, true, false, false>(g, epi, 1, 1, st);
+    mm::launch<DBM, DBN, 2, 4, true, false, false>(g, epi, 1, 1, st);
   } else {
     g.tiles_m = m / DBM;
     g.s[0].ktiles = n / DBK;
-    mm::launch<DBM, DBN, DBK, false, false, false>(g, epi, 1, 1, st);
+    mm::launch<DBM, DBN, 2, 4, false, false, false>(g, epi, 1, 1, st);
   }
 }
 

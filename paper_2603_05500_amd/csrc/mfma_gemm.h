@@ -3,19 +3,24 @@
 //
 //   C[batch] (M x N) = sum over up to two sources s of  A_s[batch] * B_s[batch]
 //
-// Each operand tile is staged in LDS exactly as it lies in memory.  An operand
-// whose contraction index is contiguous ("K major": A given as M x K, B given as
-// N x K) is fetched from LDS with 16-byte reads; one whose contraction index is
-// the strided one (A given as K x M, B given as K x N) is fetched with the
-// transposing LDS read ds_read_b64_tr_b16, which hands a lane four consecutive
-// contraction elements of a single row/column.  Rows of K-major operands may be
-// gathered through a permutation (block gradients).
+// Operand tiles go from global memory straight into LDS (global_load_lds, 16
+// bytes per lane, no staging registers) through a 4-deep ring of BK = 32 stages,
+// so three tiles are in flight while one is multiplied and the only per-tile
+// synchronisation is one barrier.  A tile is stored unpadded; bank conflicts are
+// avoided by an XOR swizzle of the 16-byte chunks, which costs nothing because
+// every lane may fetch any global chunk.
 //
-// Workgroup: 256 threads = 2 x 2 waves, wave tile (BM/2) x (BN/2), fp32
-// accumulators, double-buffered LDS stage of depth BK with the next stage's
-// global loads in flight during the multiply.  The MFMA operands are passed
-// swapped so the accumulator tile is transposed: a lane owns one output row
-// and four consecutive columns, handed to the epilogue as one float4.
+// An operand whose contraction index is contiguous in memory ("K major": A given
+// as M x K, B given as N x K) is read from LDS with 16-byte loads; one whose
+// contraction index is the strided one (A given as K x M, B given as K x N) is
+// read with the transposing LDS load ds_read_b64_tr_b16, which hands a lane four
+// consecutive contraction elements of one row/column.  Rows of K-major operands
+// may be gathered through a permutation (block gradients).
+//
+// Workgroup: WGM x WGN waves (2 x 4 for the 256 x 256 tile, i.e. two waves per SIMD),
+// wave tile (BM/WGM) x (BN/WGN), fp32 accumulators.  The MFMA operands are passed swapped so the accumulator tile is
+// transposed: a lane owns one output row and four consecutive columns, handed to
+// the epilogue as one float4.
 #pragma once
 
 #include "poetx_kernels.h"
@@ -27,37 +32,38 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef short short8v __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) short4v* lds_s4p;
 
-// Row pad of [k][x] tiles: 32 elements (64 B) spreads the four k rows one
-// transposing read touches over four different 16-bank groups.
-constexpr int PAD_T = 32;
-// Row pad of [x][k] tiles read with 16-byte loads.
-constexpr int PAD_K = 8;
+constexpr int BK = 32;       // contraction depth of one stage
+constexpr int NSTAGE = 4;    // ring depth
 
-__device__ inline short4v lds_read_tr(const uint16_t* p) {
+__device__ inline short4v lds_read_tr(const char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4p)(p));
-}
-
-// 32 x 16 operand fragment from a [k][x] tile: lane l gets column x0 + l%32,
-// contraction elements k0 + 8*(l/32) + 0..7.
-__device__ inline bf16x8 frag_from_kx(const uint16_t* tile, int stride, int k0, int x0, int lane) {
-  const int q = lane >> 4, i = lane & 15;
-  const uint16_t* p = tile + (k0 + 8 * (q >> 1) + (i >> 2)) * stride + x0 + 16 * (q & 1) + 4 * (i & 3);
-  short4v lo = lds_read_tr(p);
-  short4v hi = lds_read_tr(p + 4 * stride);
-  short8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-  return __builtin_bit_cast(bf16x8, v);
-}
-
-// Same fragment from a [x][k] tile.
-__device__ inline bf16x8 frag_from_xk(const uint16_t* tile, int stride, int k0, int x0, int lane) {
-  return *reinterpret_cast<const bf16x8*>(tile + (x0 + (lane & 31)) * stride + k0 + 8 * (lane >> 5));
 }
 
 __device__ inline uint32_t pack2_bf16(float a, float b) {
   return (uint32_t)float_to_bf16_bits(a) | ((uint32_t)float_to_bf16_bits(b) << 16);
+}
+
+// ---- swizzled tile layouts (16-byte chunk granularity) --------------------------------
+// [x][k] tile ("xk", K major): row = BK elements = 4 chunks.  16 consecutive rows read the
+// same logical chunk at once, so the chunk position is XORed with bits 2..3 of the row.
+__device__ inline int xk_chunk(int c, int row) { return c ^ ((row >> 2) & 3); }
+// [k][x] tile ("kx", K strided): row = X elements.  A transposing read touches 4
+// consecutive k rows x 2 chunks; XOR with the k row spreads them over 8 chunk positions,
+// and for wide tiles bit 1 of the chunk index is folded into bit 3 so that the two column
+// halves of a 32-wide fragment use different 128-byte halves of the bank space.
+template <int X>
+__device__ inline int kx_chunk(int c, int k) {
+  int p = c ^ (2 * (k & 3));
+  if (X >= 128) p ^= ((c >> 1) & 1) << 3;
+  return p;
+}
+template <int X>
+__device__ inline int kx_unchunk(int p, int k) {
+  int c = p ^ (2 * (k & 3));
+  if (X >= 128) c ^= ((c >> 1) & 1) << 3;   // bit 1 of c is already final here
+  return c;
 }
 
 struct Source {
@@ -65,7 +71,7 @@ struct Source {
   const uint16_t* B;
   i64 lda, ldb;        // row strides (elements)
   i64 sA, sB;          // batch strides (elements)
-  int ktiles;          // BK-deep tiles taken from this source (per split)
+  int ktiles;          // 64-deep k tiles taken from this source (per split)
 };
 
 struct Args {
@@ -76,27 +82,44 @@ struct Args {
   int rows_per_batch;
 };
 
-template <int BM, int BN, int BK, bool A_KMAJOR, bool B_KMAJOR>
+template <int BM, int BN, int WGM, int WGN>
 struct Cfg {
-  static constexpr int SA = A_KMAJOR ? BK + PAD_K : BM + PAD_T;
-  static constexpr int SB = B_KMAJOR ? BK + PAD_K : BN + PAD_T;
-  static constexpr int A_ELEMS = (A_KMAJOR ? BM : BK) * SA;
-  static constexpr int B_ELEMS = (B_KMAJOR ? BN : BK) * SB;
-  static constexpr int STAGE = A_ELEMS + B_ELEMS;
-  static constexpr size_t LDS_BYTES = (size_t)2 * STAGE * sizeof(uint16_t);
-  static constexpr int A_CHUNKS = BM * BK / 8 / 256;
-  static constexpr int B_CHUNKS = BK * BN / 8 / 256;
+  static constexpr int NWAVE = WGM * WGN;
+  static constexpr int A_BYTES = BM * BK * 2;
+  static constexpr int B_BYTES = BN * BK * 2;
+  static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+  static constexpr size_t LDS_BYTES = (size_t)NSTAGE * STAGE_BYTES;
+  static constexpr int IPW_A = A_BYTES / 1024 / NWAVE;   // direct-to-LDS instructions per wave per stage
+  static constexpr int IPW_B = B_BYTES / 1024 / NWAVE;
+  static_assert(IPW_A >= 1 && IPW_B >= 1, "tile too small for this many waves");
 };
+
+// Wait until at most N of this wave's vector-memory operations are outstanding, then
+// meet the other waves.  Written as one asm statement because __syncthreads() would
+// drain every outstanding load (it carries a full fence) and so serialise the ring; the
+// memory clobber keeps the compiler from moving LDS accesses across the barrier.
+// 16 bytes per lane from global memory straight into LDS at lds_addr + 16 * lane.  Inline
+// asm (not the builtin) so that the compiler does not drain vmcnt before later LDS reads:
+// completion is tracked by hand with wait_vmcnt_and_barrier.  lds_addr is wave uniform.
+__device__ inline void dma16(const void* gptr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
+}
+
+template <int N>
+__device__ inline void wait_vmcnt_and_barrier() {
+  static_assert(N >= 0 && N < 64, "vmcnt range");
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
 
 // Epi: __device__ void operator()(int batch, int split, int row, int col, float4 v) -- four
 // consecutive columns col..col+3 of output row `row` (indices local to the batch).
 // grid = (tiles_m * tiles_n, batches, splits).  With splits > 1 split z contracts k tiles
-// [z * ktiles, (z+1) * ktiles) of source 0.
-template <int BM, int BN, int BK, bool A_KMAJOR, bool B_KMAJOR, bool GATHER, class Epi>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(Args g, Epi epi) {
-  using C = Cfg<BM, BN, BK, A_KMAJOR, B_KMAJOR>;
-  constexpr int TM = BM / 64, TN = BN / 64;
-  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+// [z * ktiles, (z+1) * ktiles) of source 0.  Source::ktiles counts 64-deep tiles.
+template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, bool GATHER, class Epi>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(Args g, Epi epi) {
+  using C = Cfg<BM, BN, WGM, WGN>;
+  constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
 
   // Workgroups go to the 8 XCDs round robin: give each XCD a contiguous chunk of
   // the tile list (its own L2 then serves neighbouring tiles), walked in groups
@@ -112,68 +135,94 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(Args g, Epi epi) {
   const int tile_n = (wg % per_group) / gsz;
   const int batch = blockIdx.y, split = blockIdx.z;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
   const int i0 = tile_m * BM, j0 = tile_n * BN;
 
-  u32x4 ra[C::A_CHUNKS], rb[C::B_CHUNKS];
-  // Gathered rows: element offsets of this thread's rows, fixed over the k loop.
-  i64 ga[GATHER ? C::A_CHUNKS : 1], gb[GATHER ? C::B_CHUNKS : 1];
-  if (GATHER) {
-    const int32_t* pm = g.perm + (i64)batch * g.rows_per_batch;
+  // ---- global element offsets of this lane's chunk for each direct-to-LDS instruction.
+  // Instruction (wave, s) fills LDS slots [(wave*IPW + s)*64, +64) of the operand tile; the
+  // lane's slot decides, through the inverse swizzle, which global chunk it fetches.
+  i64 offA[C::IPW_A], offB[C::IPW_B];
+  {
+    const int32_t* pm = GATHER ? g.perm + (i64)batch * g.rows_per_batch : nullptr;
 #pragma unroll
-    for (int s = 0; s < C::A_CHUNKS; ++s) ga[s] = (i64)pm[i0 + (tid + s * 256) / (BK / 8)] * g.s[0].lda;
+    for (int s = 0; s < C::IPW_A; ++s) {
+      const int slot = (wave * C::IPW_A + s) * 64 + lane;
+      if (A_KMAJOR) {
+        const int r = slot >> 2, c = xk_chunk(slot & 3, r);
+        const i64 row = GATHER ? (i64)pm[i0 + r] : (i64)(i0 + r);
+        offA[s] = row * g.s[0].lda + c * 8;
+      } else {
+        constexpr int CPR = BM / 8;
+        const int k = slot / CPR, c = kx_unchunk<BM>(slot % CPR, k);
+        offA[s] = (i64)k * g.s[0].lda + i0 + c * 8;
+      }
+    }
 #pragma unroll
-    for (int s = 0; s < C::B_CHUNKS; ++s) gb[s] = (i64)pm[j0 + (tid + s * 256) / (BK / 8)] * g.s[0].ldb;
+    for (int s = 0; s < C::IPW_B; ++s) {
+      const int slot = (wave * C::IPW_B + s) * 64 + lane;
+      if (B_KMAJOR) {
+        const int r = slot >> 2, c = xk_chunk(slot & 3, r);
+        const i64 row = GATHER ? (i64)pm[j0 + r] : (i64)(j0 + r);
+        offB[s] = row * g.s[0].ldb + c * 8;
+      } else {
+        constexpr int CPR = BN / 8;
+        const int k = slot / CPR, c = kx_unchunk<BN>(slot % CPR, k);
+        offB[s] = (i64)k * g.s[0].ldb + j0 + c * 8;
+      }
+    }
   }
 
-  auto load_global = [&](const Source& src, int kt) {
-    const i64 k0 = (i64)kt * BK;
-    const uint16_t* Ab = src.A + (GATHER ? 0 : batch * src.sA);
-    const uint16_t* Bb = src.B + (GATHER ? 0 : batch * src.sB);
+  const int kt0 = g.s[0].ktiles * 2;  // in BK = 32 tiles
+  const int KT = kt0 + (g.nsrc > 1 ? g.s[1].ktiles * 2 : 0);
+  const int kbase = split * kt0;
+
+  // LDS byte address of the ring (wave uniform) for the direct-to-LDS loads
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+
+  auto issue_at = [&](int t, int ring_slot) {
+    const bool second = t >= kt0;
+    const Source& src = g.s[second ? 1 : 0];
+    const i64 kt = second ? (t - kt0) : (kbase + t);
+    const uint16_t* Ab = src.A + (GATHER ? 0 : batch * src.sA) + (A_KMAJOR ? kt * BK : kt * BK * src.lda);
+    const uint16_t* Bb = src.B + (GATHER ? 0 : batch * src.sB) + (B_KMAJOR ? kt * BK : kt * BK * src.ldb);
+    const uint32_t stage = lds_base + ring_slot * C::STAGE_BYTES;
 #pragma unroll
-    for (int s = 0; s < C::A_CHUNKS; ++s) {
-      const int c = tid + s * 256;
+    for (int s = 0; s < C::IPW_A; ++s) dma16(Ab + offA[s], stage + (wave * C::IPW_A + s) * 1024);
+#pragma unroll
+    for (int s = 0; s < C::IPW_B; ++s) dma16(Bb + offB[s], stage + C::A_BYTES + (wave * C::IPW_B + s) * 1024);
+  };
+
+  // ---- LDS byte offsets of this lane's fragments inside a stage (k step 0)
+  int fragA[TM], fragB[TN];
+  {
+    const int q = lane >> 4, i = lane & 15;
+#pragma unroll
+    for (int a = 0; a < TM; ++a) {
+      const int x0 = wm * (BM / WGM) + a * 32;
       if (A_KMAJOR) {
-        const int row = c / (BK / 8), ch = c % (BK / 8);
-        const i64 off = GATHER ? ga[s] : (i64)(i0 + row) * src.lda;
-        ra[s] = *reinterpret_cast<const u32x4*>(Ab + off + k0 + ch * 8);
+        const int r = x0 + (lane & 31);
+        fragA[a] = r * 64 + 16 * xk_chunk(lane >> 5, r);
       } else {
-        const int row = c / (BM / 8), ch = c % (BM / 8);
-        ra[s] = *reinterpret_cast<const u32x4*>(Ab + (k0 + row) * src.lda + i0 + ch * 8);
+        const int k = 8 * (q >> 1) + (i >> 2);
+        const int c = (x0 >> 3) + 2 * (q & 1) + ((i & 3) >> 1);
+        fragA[a] = k * (BM * 2) + 16 * kx_chunk<BM>(c, k) + 8 * (i & 1);
       }
     }
 #pragma unroll
-    for (int s = 0; s < C::B_CHUNKS; ++s) {
-      const int c = tid + s * 256;
+    for (int c2 = 0; c2 < TN; ++c2) {
+      const int x0 = wn * (BN / WGN) + c2 * 32;
       if (B_KMAJOR) {
-        const int row = c / (BK / 8), ch = c % (BK / 8);
-        const i64 off = GATHER ? gb[s] : (i64)(j0 + row) * src.ldb;
-        rb[s] = *reinterpret_cast<const u32x4*>(Bb + off + k0 + ch * 8);
+        const int r = x0 + (lane & 31);
+        fragB[c2] = C::A_BYTES + r * 64 + 16 * xk_chunk(lane >> 5, r);
       } else {
-        const int row = c / (BN / 8), ch = c % (BN / 8);
-        rb[s] = *reinterpret_cast<const u32x4*>(Bb + (k0 + row) * src.ldb + j0 + ch * 8);
+        const int k = 8 * (q >> 1) + (i >> 2);
+        const int c = (x0 >> 3) + 2 * (q & 1) + ((i & 3) >> 1);
+        fragB[c2] = C::A_BYTES + k * (BN * 2) + 16 * kx_chunk<BN>(c, k) + 8 * (i & 1);
       }
     }
-  };
-  auto store_lds = [&](int stage) {
-    uint16_t* As = lds + stage * C::STAGE;
-    uint16_t* Bs = As + C::A_ELEMS;
-#pragma unroll
-    for (int s = 0; s < C::A_CHUNKS; ++s) {
-      const int c = tid + s * 256;
-      const int row = A_KMAJOR ? c / (BK / 8) : c / (BM / 8);
-      const int ch = A_KMAJOR ? c % (BK / 8) : c % (BM / 8);
-      *reinterpret_cast<u32x4*>(As + row * C::SA + ch * 8) = ra[s];
-    }
-#pragma unroll
-    for (int s = 0; s < C::B_CHUNKS; ++s) {
-      const int c = tid + s * 256;
-      const int row = B_KMAJOR ? c / (BK / 8) : c / (BN / 8);
-      const int ch = B_KMAJOR ? c % (BK / 8) : c % (BN / 8);
-      *reinterpret_cast<u32x4*>(Bs + row * C::SB + ch * 8) = rb[s];
-    }
-  };
+  }
 
   floatx16 acc[TM][TN];
 #pragma unroll
@@ -183,60 +232,78 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(Args g, Epi epi) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][c][v] = 0.f;
 
-  // k tiles of source 0 then source 1, as one sequence
-  const int kt0 = g.s[0].ktiles;
-  const int KT = kt0 + (g.nsrc > 1 ? g.s[1].ktiles : 0);
-  const int kbase = split * kt0;
-  auto fetch = [&](int kt) {
-    if (kt < kt0) load_global(g.s[0], kbase + kt);
-    else load_global(g.s[1], kt - kt0);
+  auto load_frag = [&](const char* stage, int off, bool kmajor, int row_bytes, int ks) -> bf16x8 {
+    if (kmajor) {
+      // k step 1 is logical chunk + 2: flips bit 1 of the swizzled position
+      return *reinterpret_cast<const bf16x8*>(stage + (ks ? (off ^ 32) : off));
+    }
+    const char* p = stage + off + ks * 16 * row_bytes;
+    short4v lo = lds_read_tr(p);
+    short4v hi = lds_read_tr(p + 4 * row_bytes);
+    short8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+  };
+  struct Frags {
+    bf16x8 a[TM], b[TN];
+  };
+  auto load_frags = [&](Frags& f, int t, int ks) {
+    const char* stage = lds + (t % NSTAGE) * C::STAGE_BYTES;
+#pragma unroll
+    for (int a = 0; a < TM; ++a) f.a[a] = load_frag(stage, fragA[a], A_KMAJOR, BM * 2, ks);
+#pragma unroll
+    for (int c = 0; c < TN; ++c) f.b[c] = load_frag(stage, fragB[c], B_KMAJOR, BN * 2, ks);
+  };
+  auto mfma_all = [&](const Frags& f) {
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+      for (int c = 0; c < TN; ++c)
+        acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[c], f.a[a], acc[a][c], 0, 0, 0);
   };
 
-  auto multiply = [&](int stage) {
-    const uint16_t* As = lds + stage * C::STAGE;
-    const uint16_t* Bs = As + C::A_ELEMS;
-#pragma unroll 2
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 fa[TM], fb[TN];
+  // Ask the scheduler to alternate one MFMA with one LDS read (0x008 = MFMA, 0x100 = DS read)
+  // so the fragment reads of the next k step trickle in under the current MFMAs.
+  auto interleave_hint = [&]() {
 #pragma unroll
-      for (int a = 0; a < TM; ++a) {
-        const int x0 = wm * (BM / 2) + a * 32;
-        fa[a] = A_KMAJOR ? frag_from_xk(As, C::SA, ks * 16, x0, lane) : frag_from_kx(As, C::SA, ks * 16, x0, lane);
-      }
-#pragma unroll
-      for (int c = 0; c < TN; ++c) {
-        const int x0 = wn * (BN / 2) + c * 32;
-        fb[c] = B_KMAJOR ? frag_from_xk(Bs, C::SB, ks * 16, x0, lane) : frag_from_kx(Bs, C::SB, ks * 16, x0, lane);
-      }
-#pragma unroll
-      for (int a = 0; a < TM; ++a)
-#pragma unroll
-        for (int c = 0; c < TN; ++c)
-          acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c], fa[a], acc[a][c], 0, 0, 0);
+    for (int i = 0; i < TM * TN; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
   };
 
-  // The last tile is peeled so that the loads inside the loop are unconditional: the
-  // staging registers then have a single definition per iteration and nothing has to
-  // wait for them before the multiply.
-  fetch(0);
-  store_lds(0);
-  __syncthreads();
-  for (int kt = 0; kt + 1 < KT; ++kt) {
-    fetch(kt + 1);
-    multiply(kt & 1);
-    store_lds((kt & 1) ^ 1);
-    __syncthreads();
+  // Ring schedule.  Tiles kt+1 .. kt+NSTAGE-1 are in flight or landed while tile kt is
+  // multiplied.  At the top of iteration kt the wave waits for tile kt+1 (one tile ahead,
+  // so that its first fragments can be prefetched under the last MFMAs of tile kt), meets
+  // the other waves, and refills the stage that tile kt-1 has just vacated.
+  constexpr int LPT = C::IPW_A + C::IPW_B;  // direct-to-LDS loads per tile per wave
+  // Loads past the last tile re-fetch the last tile into a free stage: that keeps the
+  // number of outstanding loads constant, so the loop body has no branches and one
+  // fixed vmcnt threshold.
+  auto issue_clamped = [&](int t) { issue_at(t < KT ? t : KT - 1, t % NSTAGE); };
+#pragma unroll
+  for (int t = 0; t < NSTAGE - 1; ++t) issue_clamped(t);
+  wait_vmcnt_and_barrier<(NSTAGE - 2) * LPT>();
+  Frags F, G;
+  load_frags(F, 0, 0);
+  for (int kt = 0; kt < KT; ++kt) {
+    wait_vmcnt_and_barrier<(NSTAGE - 3) * LPT>();   // tile kt+1 has landed, for every wave
+    issue_clamped(kt + NSTAGE - 1);                 // into the stage tile kt-1 vacated
+    load_frags(G, kt, 1);
+    mfma_all(F);
+    interleave_hint();
+    load_frags(F, kt + 1, 0);                       // stale but harmless after the last tile
+    mfma_all(G);
+    interleave_hint();
   }
-  multiply((KT - 1) & 1);
+  wait_vmcnt_and_barrier<0>();
 
   const int h = lane >> 5, li = lane & 31;
 #pragma unroll
   for (int a = 0; a < TM; ++a) {
-    const int row = i0 + wm * (BM / 2) + a * 32 + li;
+    const int row = i0 + wm * (BM / WGM) + a * 32 + li;
 #pragma unroll
     for (int c = 0; c < TN; ++c) {
-      const int col = j0 + wn * (BN / 2) + c * 32 + 4 * h;
+      const int col = j0 + wn * (BN / WGN) + c * 32 + 4 * h;
 #pragma unroll
       for (int q = 0; q < 4; ++q)
         epi(batch, split, row, col + 8 * q,
@@ -245,16 +312,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(Args g, Epi epi) {
   }
 }
 
-template <int BM, int BN, int BK, bool A_KMAJOR, bool B_KMAJOR, bool GATHER, class Epi>
+template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, bool GATHER, class Epi>
 void launch(const Args& g, Epi epi, int batches, int splits, hipStream_t st) {
-  using C = Cfg<BM, BN, BK, A_KMAJOR, B_KMAJOR>;
-  auto kern = gemm_bf16_kernel<BM, BN, BK, A_KMAJOR, B_KMAJOR, GATHER, Epi>;
+  using C = Cfg<BM, BN, WGM, WGN>;
+  auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, A_KMAJOR, B_KMAJOR, GATHER, Epi>;
   static bool configured = false;
   if (!configured) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
     configured = true;
   }
-  hipLaunchKernelGGL(kern, dim3(g.tiles_m * g.tiles_n, batches, splits), dim3(256), C::LDS_BYTES, st, g, epi);
+  hipLaunchKernelGGL(kern, dim3(g.tiles_m * g.tiles_n, batches, splits), dim3(64 * WGM * WGN), C::LDS_BYTES, st, g, epi);
 }
 
 // Plain bf16 store of the output tile.
