@@ -31,6 +31,9 @@ def parse():
                     help="llama8b-b256 (default, the metric's configuration), llama8b-b512, llama3b, llama1b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=128, help="tokens in the oracle's timed sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run one plain 1 GiB device-to-device copy first (a known-size kernel for scaling "
+                         "FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
     return ap.parse_args()
 
 
@@ -157,6 +160,12 @@ def main():
             px.poetx_linear_bwd_skew(p["desc"], p["X"], p["dZ"], B[:n], dA[:m], p["pi_R"], p["pi_P"],
                                      p["theta_R"], p["theta_P"], p["dtheta_R"], p["dtheta_P"], False, ws)
 
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
