@@ -20,6 +20,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# L2<->fabric bytes per dense launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by
+# what the same counters read for a 1 GiB copy (2.0 and 1.0); see profiles/llama8b_b256_layer_counters.md.
+DENSE_TRAFFIC_BYTES_PER_LAUNCH = {"llama8b-b256": 1.71e9}
 
 
 def parse():
@@ -212,7 +215,7 @@ def main():
         },
         "roofline": {"bound": "mfma", "kernel": "dense bf16 product (B = W A, dA = W^T dB)",
                      "achieved": dense_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": dense_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": dense_tflops / PEAK_BF16_TFLOPS, "traffic": DENSE_TRAFFIC_BYTES_PER_LAUNCH.get(cfg.name),
                      "launches": int(dense_cnt), "avg_launch_ms": dense_ms / max(int(dense_cnt), 1)},
     }
     if not args.no_cpu_baseline:
