@@ -129,6 +129,161 @@ __global__ __launch_bounds__(256) void apply_left_bf16_kernel(const uint16_t* __
   }
 }
 
+
+// ---------------------------------------------------------------------------------------
+// Streaming variant for b = 256: one persistent workgroup per (block, token range).
+//   * 8 waves; wave w owns block rows [32w, 32w+32) for loading, computing and storing.
+//   * op(E_j) rows of the wave stay in registers as matrix-core fragments for the whole range
+//     (16 k steps x 4 VGPRs), so the block operand is read once per workgroup.
+//   * token tiles of 128 go from HBM straight into a 2-stage LDS ring (global_load_lds, rows
+//     gathered through the permutation, XOR-swizzled chunks, no bank conflicts); the tile of
+//     the next step is in flight while the current one is multiplied.
+//   * the identity part of G is applied as one exact extra MFMA per k step that covers the
+//     wave's own rows (1.0 * x accumulates exactly in fp32), so nothing is re-read.
+//   * results leave from registers: a lane owns one row and 4 consecutive tokens (8-byte
+//     packed stores), scattered through the same index map that gathered them.
+constexpr int SBN = 128;                      // tokens per tile
+constexpr int S_STAGE_BYTES = 256 * SBN * 2;  // 64 KB
+
+__global__ __launch_bounds__(512) void apply_left_stream256_kernel(const uint16_t* __restrict__ V,
+                                                                    uint16_t* __restrict__ out, i64 ld,
+                                                                    const int32_t* __restrict__ perm,
+                                                                    const uint16_t* __restrict__ blocks, int trans,
+                                                                    int tiles_per_wg) {
+  constexpr int B = 256, TN = SBN / 32, KS = B / 16;
+  extern __shared__ __attribute__((aligned(1024))) char ring[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int j = blockIdx.y;
+  const i64 tok0 = (i64)blockIdx.x * tiles_per_wg * SBN;
+  const int32_t* pm = perm + (i64)j * B;
+  const int li = lane & 31, h = lane >> 5;
+  const uint32_t ring_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)ring;
+
+  // direct-to-LDS instruction s of this wave fills chunk slots [(8w+s)*64, +64) of a stage:
+  // row k = 32w + 4s + lane/16, chunk position lane%16 -> logical chunk through the swizzle.
+  i64 goff[8];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    const int k = wave * 32 + s * 4 + (lane >> 4);
+    const int c = mm::kx_unchunk<SBN>(lane & 15, k);
+    goff[s] = (i64)pm[k] * ld + tok0 + c * 8;
+  }
+  auto issue = [&](int t) {
+    const uint32_t stage = ring_base + (t & 1) * S_STAGE_BYTES + wave * 8 * 1024;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) mm::dma16(V + goff[s] + (i64)t * SBN, stage + s * 1024);
+  };
+  issue(0);
+
+  // block operand fragments (rows of op(E_j) are contiguous in the stored pair)
+  const uint16_t* Eb = blocks + ((i64)j * 2 + (trans ? 1 : 0)) * B * B + (i64)(wave * 32 + li) * B + 8 * h;
+  bf16x8 fa[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) fa[ks] = *reinterpret_cast<const bf16x8*>(Eb + ks * 16);
+  // identity fragments for the two k steps that cover rows [32w, 32w+32)
+  bf16x8 fi[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) fi[u][e] = (li == u * 16 + 8 * h + e) ? (__bf16)1.0f : (__bf16)0.0f;
+
+  // LDS byte offsets of this lane's token fragments at k step 0
+  int fragB[TN];
+  {
+    const int q = lane >> 4, i = lane & 15;
+    const int k = 8 * (q >> 1) + (i >> 2);
+#pragma unroll
+    for (int c2 = 0; c2 < TN; ++c2) {
+      const int c = c2 * 4 + 2 * (q & 1) + ((i & 3) >> 1);
+      fragB[c2] = k * (SBN * 2) + 16 * mm::kx_chunk<SBN>(c, k) + 8 * (i & 1);
+    }
+  }
+  // store offsets: row 32w + li, tokens c*32 + 8q + 4h
+  const i64 soff = (i64)pm[wave * 32 + li] * ld + tok0 + 4 * h;
+
+  // The packed results of a tile are stored one iteration late, right after the next barrier:
+  // by the following barrier both those stores and the loads of the next tile are old, so a
+  // plain vmcnt(0) there waits for nothing that is not already due (loads and stores share
+  // one counter and may retire out of order with respect to each other).
+  uint2 pend[TN * 4];
+  auto flush = [&](int t) {
+    uint16_t* o = out + soff + (i64)t * SBN;
+#pragma unroll
+    for (int c = 0; c < TN; ++c)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) *reinterpret_cast<uint2*>(o + c * 32 + 8 * q) = pend[c * 4 + q];
+  };
+  for (int t = 0; t < tiles_per_wg; ++t) {
+    // tile t has landed and every wave is done reading the stage that tile t+1 overwrites
+    mm::wait_vmcnt_and_barrier<0>();
+    if (t > 0) flush(t - 1);
+    if (t + 1 < tiles_per_wg) issue(t + 1);
+    const char* stage = ring + (t & 1) * S_STAGE_BYTES;
+    floatx16 acc[TN];
+#pragma unroll
+    for (int c = 0; c < TN; ++c)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      bf16x8 fb[TN];
+#pragma unroll
+      for (int c = 0; c < TN; ++c) {
+        const char* p = stage + fragB[c] + ks * 16 * (SBN * 2);
+        short4v lo = mm::lds_read_tr(p);
+        short4v hi = mm::lds_read_tr(p + 4 * (SBN * 2));
+        short8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        fb[c] = __builtin_bit_cast(bf16x8, v);
+      }
+#pragma unroll
+      for (int c = 0; c < TN; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c], fa[ks], acc[c], 0, 0, 0);
+      if ((ks >> 1) == wave) {  // wave uniform: these 16 l values lie in the wave's own rows
+#pragma unroll
+        for (int c = 0; c < TN; ++c)
+          acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c], fi[ks & 1], acc[c], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < TN; ++c)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        pend[c * 4 + q].x = mm::pack2_bf16(acc[c][4 * q + 0], acc[c][4 * q + 1]);
+        pend[c * 4 + q].y = mm::pack2_bf16(acc[c][4 * q + 2], acc[c][4 * q + 3]);
+      }
+  }
+  flush(tiles_per_wg - 1);
+}
+
+// token ranges per block: fill the 256 CUs in whole rounds, at least 2 tiles per workgroup
+int stream_chunks(int nb, int tiles) {
+  int best = 1;
+  double best_eff = 0.0;
+  for (int c = 1; c <= tiles; c *= 2) {
+    if (tiles % c != 0 || tiles / c < 2) break;
+    const double wgs = (double)nb * c;
+    const double rounds = (wgs + 255) / 256;
+    const double eff = wgs / 256.0 / (double)(long long)rounds;
+    if (eff > best_eff + 1e-9) { best_eff = eff; best = c; }
+  }
+  return best;
+}
+
+void launch_apply_stream256(const uint16_t* V, uint16_t* out, int d, i64 cols, i64 ld, const int32_t* perm,
+                            const uint16_t* E, int trans, hipStream_t st) {
+  constexpr size_t LDS = 2 * (size_t)S_STAGE_BYTES;
+  static bool configured = false;
+  if (!configured) {
+    (void)hipFuncSetAttribute((const void*)apply_left_stream256_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)LDS);
+    configured = true;
+  }
+  const int nb = d / 256, tiles = (int)(cols / SBN);
+  const int chunks = stream_chunks(nb, tiles);
+  hipLaunchKernelGGL(apply_left_stream256_kernel, dim3(chunks, nb), dim3(512), LDS, st, V, out, ld, perm, E, trans,
+                     tiles / chunks);
+}
+
 template <int B, int BN>
 void launch_apply(const uint16_t* V, uint16_t* out, int d, i64 cols, i64 ld, const int32_t* perm, const uint16_t* E,
                   int trans, hipStream_t st) {
@@ -155,7 +310,9 @@ bool mfma_apply_left_supported(int d, i64 cols, i64 ld, int b) {
 
 void mfma_apply_left(const void* V, void* out, int d, i64 cols, i64 ld, const int32_t* perm, const void* E, int b,
                      int transpose_G, hipStream_t st) {
-  if (b == 256)
+  if (b == 256 && cols % (2 * SBN) == 0)
+    launch_apply_stream256((const uint16_t*)V, (uint16_t*)out, d, cols, ld, perm, (const uint16_t*)E, transpose_G, st);
+  else if (b == 256)
     launch_apply<256, BN256>((const uint16_t*)V, (uint16_t*)out, d, cols, ld, perm, (const uint16_t*)E, transpose_G, st);
   else
     launch_apply<512, BN512>((const uint16_t*)V, (uint16_t*)out, d, cols, ld, perm, (const uint16_t*)E, transpose_G, st);
