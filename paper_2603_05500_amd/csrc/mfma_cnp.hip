@@ -4,15 +4,14 @@
 // Every b x b product runs as bf16 x bf16 -> fp32 on the batched tile kernel.  To
 // keep the small terms, the chain is carried in residual form: with H = 2I + H'
 // Horner's rule H <- H Q + 2I becomes H' <- 2Q + H' Q, where only the small
-// product H' Q goes through bf16 and the 2Q term is added in fp32 from theta.
+// product H' Q goes through bf16 and the 2Q term is added in fp32.
 // After k steps H' is G - I.  The backward recursion (see fma_cnp_bwd) is carried
 // the same way: A = 2I + A', A' <- 2T + A' T and Bm <- 2D + A' D + Bm T with
-// T = -Q, the 2D term added in fp32.
+// T = -Q, the 2D term added in fp32; the two products of one step are independent
+// and share one launch.
 #include "mfma_gemm.h"
 
 namespace poetx {
-void skew_project_launch(const float* M, int b, int d, float* dtheta, int accumulate, hipStream_t st);
-
 namespace {
 
 // Small output tiles: one side has only a few blocks, so 64 x 64 tiles are what fills the 256 CUs.
@@ -23,15 +22,16 @@ __device__ inline float skew_at(const float* th, int i, int c, int b) {
   return i < c ? th[packed_index(i, c, b)] : -th[packed_index(c, i, b)];
 }
 
-// Qb = bf16(Q), Tb = bf16(-Q) for every block.
-__global__ void skew_materialize_kernel(const float* __restrict__ theta, int b, i64 total, uint16_t* __restrict__ Qb,
-                                        uint16_t* __restrict__ Tb) {
+// Q from the packed parameters: Qf = Q (fp32), Qb = bf16(Q), Tb = bf16(-Q); any may be null.
+__global__ void skew_materialize_kernel(const float* __restrict__ theta, int b, i64 total, float* __restrict__ Qf,
+                                        uint16_t* __restrict__ Qb, uint16_t* __restrict__ Tb) {
   i64 idx = (i64)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= total) return;
   int c = (int)(idx % b);
   int i = (int)((idx / b) % b);
   i64 j = idx / ((i64)b * b);
   float q = skew_at(theta + j * ((i64)b * (b - 1) / 2), i, c, b);
+  if (Qf) Qf[idx] = q;
   if (Qb) Qb[idx] = float_to_bf16_bits(q);
   if (Tb) Tb[idx] = float_to_bf16_bits(-q);
 }
@@ -46,21 +46,19 @@ __global__ void to_bf16_kernel(const float4* __restrict__ in, uint2* __restrict_
   out[idx] = o;
 }
 
-// value = acc + 2 * sign * skew(theta)(row, col).  Writes whichever outputs are set:
+// value = acc + coef * Qf(row, col).  Writes whichever outputs are set:
 // Hn (bf16 chain value), G (fp32, + I), E (bf16 pair [nb][2][b][b]: value and its transpose).
 struct EpiHorner {
-  const float* theta;
-  float sign;
+  const float* Qf;
+  float coef;
   int b;
   uint16_t* Hn;
   float* G;
   uint16_t* E;
   __device__ void operator()(int j, int, int row, int col, float4 a) const {
-    const float* th = theta + (i64)j * ((i64)b * (b - 1) / 2);
-    float v[4] = {a.x, a.y, a.z, a.w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] += 2.f * sign * skew_at(th, row, col + e, b);
     const i64 o = ((i64)j * b + row) * b + col;
+    const float4 q = *reinterpret_cast<const float4*>(Qf + o);
+    float v[4] = {a.x + coef * q.x, a.y + coef * q.y, a.z + coef * q.z, a.w + coef * q.w};
     uint2 pk;
     pk.x = mm::pack2_bf16(v[0], v[1]);
     pk.y = mm::pack2_bf16(v[2], v[3]);
@@ -82,23 +80,31 @@ struct EpiHorner {
   }
 };
 
-// value = acc + 2 * D(row, col): next chain value in bf16 and/or the final fp32 result.
-struct EpiBwd {
+// One backward step in one launch.  Batches [0, nb): Bm_next = acc + 2 D  (bf16 chain value and/or
+// the final fp32 result).  Batches [nb, 2nb): A'_next = acc - 2 Q (bf16).
+struct EpiBwdStep {
   const float* D;
-  int b;
+  const float* Qf;
+  int b, nb;
   uint16_t* Bn;
   float* Bf;
-  __device__ void operator()(int j, int, int row, int col, float4 a) const {
+  uint16_t* An;
+  __device__ void operator()(int batch, int, int row, int col, float4 a) const {
+    const bool second = batch >= nb;
+    const int j = second ? batch - nb : batch;
     const i64 o = ((i64)j * b + row) * b + col;
-    float4 d = *reinterpret_cast<const float4*>(D + o);
-    float4 v = make_float4(a.x + 2.f * d.x, a.y + 2.f * d.y, a.z + 2.f * d.z, a.w + 2.f * d.w);
-    if (Bn) {
-      uint2 pk;
-      pk.x = mm::pack2_bf16(v.x, v.y);
-      pk.y = mm::pack2_bf16(v.z, v.w);
-      *reinterpret_cast<uint2*>(Bn + o) = pk;
+    const float4 d = *reinterpret_cast<const float4*>((second ? Qf : D) + o);
+    const float coef = second ? -2.f : 2.f;
+    const float4 v = make_float4(a.x + coef * d.x, a.y + coef * d.y, a.z + coef * d.z, a.w + coef * d.w);
+    uint2 pk;
+    pk.x = mm::pack2_bf16(v.x, v.y);
+    pk.y = mm::pack2_bf16(v.z, v.w);
+    if (second) {
+      *reinterpret_cast<uint2*>(An + o) = pk;
+    } else {
+      if (Bn) *reinterpret_cast<uint2*>(Bn + o) = pk;
+      if (Bf) *reinterpret_cast<float4*>(Bf + o) = v;
     }
-    if (Bf) *reinterpret_cast<float4*>(Bf + o) = v;
   }
 };
 
@@ -116,13 +122,18 @@ void set_src(mm::Source& s, const uint16_t* A, const uint16_t* B, int b) {
 
 bool mfma_cnp_supported(int d, int b) { return (b == 256 || b == 512) && d % b == 0; }
 
-// ws: Qb | H0 | H1, bf16 nb*b*b each.
+// bytes of scratch per block element (nb*b*b elements): forward Qf(4) + Qb, H0, H1 (2 each);
+// backward Qf(4) + Tb, Db, A0, A1, B0, B1 (2 each) + Bfinal(4).
+size_t mfma_cnp_build_ws_bytes_per_elem() { return 10; }
+size_t mfma_cnp_bwd_ws_bytes_per_elem() { return 20; }
+
 void mfma_cnp_build(const float* theta, int d, int b, int k, float* G_f32, void* E_bf16, float* ws, hipStream_t st) {
   const int nb = d / b;
   const i64 total = (i64)nb * b * b;
-  uint16_t* Qb = (uint16_t*)ws;
+  float* Qf = ws;
+  uint16_t* Qb = (uint16_t*)(Qf + total);
   uint16_t* H[2] = {Qb + total, Qb + 2 * total};
-  hipLaunchKernelGGL(skew_materialize_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, theta, b, total, Qb,
+  hipLaunchKernelGGL(skew_materialize_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, theta, b, total, Qf, Qb,
                      (uint16_t*)nullptr);
   const uint16_t* cur = Qb;  // H'_1 = Q
   for (int step = 0; step < k; ++step) {
@@ -131,23 +142,23 @@ void mfma_cnp_build(const float* theta, int d, int b, int k, float* G_f32, void*
     g.nsrc = 1;
     set_src(g.s[0], cur, Qb, b);
     uint16_t* nxt = H[step & 1];
-    EpiHorner epi{theta, 1.f, b, last ? nullptr : nxt, last ? G_f32 : nullptr, last ? (uint16_t*)E_bf16 : nullptr};
+    EpiHorner epi{Qf, 2.f, b, last ? nullptr : nxt, last ? G_f32 : nullptr, last ? (uint16_t*)E_bf16 : nullptr};
     mm::launch<CBM, CBN, 2, 2, true, false, false>(g, epi, nb, 1, st);
     cur = nxt;
   }
 }
 
-// ws: Tb | Db | A0 | A1 | B0 | B1 (bf16 nb*b*b each) | Bfinal (fp32 nb*b*b)  = 4 floats per element.
 void mfma_cnp_bwd(const float* theta, const float* dG, int d, int b, int k, float* dtheta, int accumulate, float* ws,
                   hipStream_t st) {
   const int nb = d / b;
   const i64 total = (i64)nb * b * b;
-  uint16_t* Tb = (uint16_t*)ws;
+  float* Qf = ws;
+  float* Bfinal = Qf + total;
+  uint16_t* Tb = (uint16_t*)(Bfinal + total);
   uint16_t* Db = Tb + total;
   uint16_t* A[2] = {Tb + 2 * total, Tb + 3 * total};
   uint16_t* Bb[2] = {Tb + 4 * total, Tb + 5 * total};
-  float* Bfinal = (float*)(Tb + 6 * total);
-  hipLaunchKernelGGL(skew_materialize_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, theta, b, total,
+  hipLaunchKernelGGL(skew_materialize_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, theta, b, total, Qf,
                      (uint16_t*)nullptr, Tb);
   hipLaunchKernelGGL(to_bf16_kernel, dim3(ceil_div(total / 4, 256)), dim3(256), 0, st, (const float4*)dG, (uint2*)Db,
                      total / 4);
@@ -160,14 +171,14 @@ void mfma_cnp_bwd(const float* theta, const float* dG, int d, int b, int k, floa
     g.nsrc = 2;
     set_src(g.s[0], acur, Db, b);  // A' D
     set_src(g.s[1], bcur, Tb, b);  // Bm T
-    EpiBwd epi{dG, b, last ? nullptr : Bb[ib], last ? Bfinal : nullptr};
-    mm::launch<CBM, CBN, 2, 2, true, false, false>(g, epi, nb, 1, st);
+    if (!last) {                   // second problem of the launch: A' T
+      g.alt_from = nb;
+      g.alt_nsrc = 1;
+      set_src(g.alt[0], acur, Tb, b);
+    }
+    EpiBwdStep epi{dG, Qf, b, nb, last ? nullptr : Bb[ib], last ? Bfinal : nullptr, last ? nullptr : A[ia]};
+    mm::launch<CBM, CBN, 2, 2, true, false, false>(g, epi, last ? nb : 2 * nb, 1, st);
     if (!last) {
-      mm::Args h = batched_args(b);
-      h.nsrc = 1;
-      set_src(h.s[0], acur, Tb, b);  // A' T
-      EpiHorner eh{theta, -1.f, b, A[ia], nullptr, nullptr};
-      mm::launch<CBM, CBN, 2, 2, true, false, false>(h, eh, nb, 1, st);
       acur = A[ia];
       ia ^= 1;
       bcur = Bb[ib];

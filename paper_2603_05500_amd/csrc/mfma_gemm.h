@@ -77,6 +77,12 @@ struct Source {
 struct Args {
   Source s[2];
   int nsrc;
+  // Optional second problem in the same launch: batches >= alt_from run it (with batch index
+  // batch - alt_from for the operand strides; the epilogue still sees the raw batch index).
+  // Same tile shape, strides and layout flags as the first; alt_from = 0 disables it.
+  Source alt[2];
+  int alt_nsrc;
+  int alt_from;
   int tiles_m, tiles_n;      // output tiles per batch
   const int32_t* perm;       // GATHER: row r of batch j of both operands is memory row perm[j*rows_per_batch + r]
   int rows_per_batch;
@@ -174,8 +180,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(Args g, Epi e
     }
   }
 
-  const int kt0 = g.s[0].ktiles * 2;  // in BK = 32 tiles
-  const int KT = kt0 + (g.nsrc > 1 ? g.s[1].ktiles * 2 : 0);
+  const bool use_alt = g.alt_from > 0 && batch >= g.alt_from;
+  const Source* S = use_alt ? g.alt : g.s;
+  const int nsrc = use_alt ? g.alt_nsrc : g.nsrc;
+  const int bidx = use_alt ? batch - g.alt_from : batch;
+  const int kt0 = S[0].ktiles * 2;  // in BK = 32 tiles
+  const int KT = kt0 + (nsrc > 1 ? S[1].ktiles * 2 : 0);
   const int kbase = split * kt0;
 
   // LDS byte address of the ring (wave uniform) for the direct-to-LDS loads
@@ -183,10 +193,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(Args g, Epi e
 
   auto issue_at = [&](int t, int ring_slot) {
     const bool second = t >= kt0;
-    const Source& src = g.s[second ? 1 : 0];
+    const Source& src = S[second ? 1 : 0];
     const i64 kt = second ? (t - kt0) : (kbase + t);
-    const uint16_t* Ab = src.A + (GATHER ? 0 : batch * src.sA) + (A_KMAJOR ? kt * BK : kt * BK * src.lda);
-    const uint16_t* Bb = src.B + (GATHER ? 0 : batch * src.sB) + (B_KMAJOR ? kt * BK : kt * BK * src.ldb);
+    const uint16_t* Ab = src.A + (GATHER ? 0 : bidx * src.sA) + (A_KMAJOR ? kt * BK : kt * BK * src.lda);
+    const uint16_t* Bb = src.B + (GATHER ? 0 : bidx * src.sB) + (B_KMAJOR ? kt * BK : kt * BK * src.ldb);
     const uint32_t stage = lds_base + ring_slot * C::STAGE_BYTES;
 #pragma unroll
     for (int s = 0; s < C::IPW_A; ++s) dma16(Ab + offA[s], stage + (wave * C::IPW_A + s) * 1024);

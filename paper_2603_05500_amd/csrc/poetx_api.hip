@@ -32,8 +32,8 @@ int check_desc(const poetx_linear_desc* d) {
   return POETX_OK;
 }
 
-// dG plus four chain buffers of nb*b*b floats
-size_t cnp_bwd_ws_floats(int d, int b) { return (size_t)5 * ceil_div(d, b) * b * b; }
+// dG plus chain scratch: five floats per block element cover both kernel families
+size_t cnp_bwd_ws_floats(int d, int b) { return (size_t)6 * ceil_div(d, b) * b * b; }
 
 void apply_left_dispatch(int dtype, const void* V, void* out, int d, i64 cols, i64 ld, const int32_t* perm,
                          const void* blocks, int b, int trans, hipStream_t st) {
@@ -80,7 +80,7 @@ void poetx_debug_force_fma(int on) { g_force_fma.store(on ? 1 : 0); }
 
 size_t poetx_cnp_workspace_bytes(int32_t d, int32_t b) {
   if (d <= 0 || b <= 0) return 0;
-  return align256((size_t)2 * ceil_div(d, b) * b * b * sizeof(float));
+  return align256((size_t)3 * ceil_div(d, b) * b * b * sizeof(float));  // covers both kernel families
 }
 
 int poetx_cnp_build(const float* theta, int32_t d, int32_t b, int32_t k, int32_t precision, float* G_f32,
