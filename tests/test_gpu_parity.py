@@ -232,3 +232,32 @@ def test_bf16_layer_matrix_core_shapes(lib, m, n, N, b, k):
     finally:
         lib.poetx_debug_force_fma(False)
     check_layer(res2, ref, data["pi_P"], "bf16")
+
+
+# ------------------------------------------------------------------ merge step W <- R W P
+@pytest.mark.parametrize("m,n,b,dtype", [(256, 512, 256, "bf16"), (96, 160, 32, "f32"), (1376, 512, 64, "bf16")])
+def test_merge_step(lib, m, n, b, dtype):
+    """The periodic merge (Sec. 3, after Eq. 2): W_i = R W_{i-1} P.  On the stored weight W = W0^T this is
+    W_new = P^T W R^T = apply_right(apply_left(W, P^T), R^T); checked against the dense definition, and
+    a forward pass with the merged weight and zero parameters must reproduce the un-merged forward."""
+    rng = RNG(9000 + m + n + b)
+    rnd = round_f32 if dtype == "f32" else round_bf16
+    k, N = 4, 256
+    W = rnd(rng.standard_normal((n, m)) * 0.02)
+    X = rnd(rng.standard_normal((m, N)))
+    th_R, th_P = draw_theta(rng, m, b, 0.01), draw_theta(rng, n, b, 0.01)
+    pi_R, pi_P = rng.permutation(m).astype(np.int32), rng.permutation(n).astype(np.int32)
+    blk_R, G_R = build_blocks(th_R, m, b, k, dtype, lib.CNP_FP32)
+    blk_P, G_P = build_blocks(th_P, n, b, k, dtype, lib.CNP_FP32)
+    dt = tdtype(dtype)
+    Wd = to_dev(W, dt)
+    tmp, Wn = torch.empty_like(Wd), torch.empty_like(Wd)
+    pR, pP = torch.from_numpy(pi_R).cuda(), torch.from_numpy(pi_P).cuda()
+    lib.poetx_perm_blockdiag_apply_left(Wd, tmp, pP, blk_P, b, True)      # P^T W
+    lib.poetx_perm_blockdiag_apply_right(tmp, Wn, pR, blk_R, b, True)     # (P^T W) R^T
+    torch.cuda.synchronize()
+    Zd, W_eff = orc.linear_fwd_dense(X, W, pi_R, pi_P, orc.cnp(orc.skew_from_packed(th_R, b, m), k),
+                                     orc.cnp(orc.skew_from_packed(th_P, b, n), k))
+    assert rel_err(to_np(Wn), W_eff.T) <= TOL[dtype]
+    # mergeability: plain product with the merged weight == POET-X forward with the factors
+    assert rel_err(to_np(Wn) @ X, Zd) <= 2 * TOL[dtype]
