@@ -32,6 +32,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama8b-b256",
                     help="llama8b-b256 (default, the metric's configuration), llama8b-b512, llama3b, llama1b")
+    ap.add_argument("--variant", default="fast", choices=["fast", "mem"],
+                    help="fast keeps B from the forward pass (the measured metric); mem recomputes it in backward")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=128, help="tokens in the oracle's timed sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -142,7 +144,8 @@ def main():
     dA = torch.empty((mmax, N), device="cuda", dtype=dt)
     ws_bytes = cnp_bytes = 0
     for p in projs:
-        p["desc"] = px.make_desc(p["m"], p["n"], b, k, N, code)
+        p["desc"] = px.make_desc(p["m"], p["n"], b, k, N, code,
+                                 flags=px.FLAG_RECOMPUTE_B if args.variant == "mem" else 0)
         ws_bytes = max(ws_bytes, px.poetx_linear_workspace_bytes(p["desc"]))
         cnp_bytes = max(cnp_bytes, px.poetx_cnp_workspace_bytes(max(p["m"], p["n"]), b))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
@@ -157,9 +160,11 @@ def main():
             kw = {"E_bf16": p["blk_P"]} if code == px.BF16 else {"G_f32": p["blk_P"]}
             px.poetx_cnp_build(p["theta_P"], n, b, k, prec, ws=cws, **kw)
             px.poetx_linear_fwd(p["desc"], p["X"], p["W"], p["pi_R"], p["pi_P"], p["blk_R"], p["blk_P"],
-                                Z[:n], B[:n], ws)
+                                Z[:n], None if args.variant == "mem" else B[:n], ws)
             px.poetx_linear_bwd_input(p["desc"], p["dZ"], p["W"], p["pi_R"], p["pi_P"], p["blk_R"], p["blk_P"],
                                       dX[:m], dA[:m], ws)
+            if args.variant == "mem":
+                px.poetx_linear_recompute_b(p["desc"], p["X"], p["W"], p["pi_R"], p["blk_R"], B[:n], ws)
             px.poetx_linear_bwd_skew(p["desc"], p["X"], p["dZ"], B[:n], dA[:m], p["pi_R"], p["pi_P"],
                                      p["theta_R"], p["theta_P"], p["dtheta_R"], p["dtheta_P"], False, ws)
 
@@ -202,7 +207,7 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: one decoder layer = 7 POET-X linears "
                                f"({', '.join(f'{p.name} {p.d_out}x{p.d_in}' for p in cfg.projections)}), "
-                               f"N={N} tokens, b={b}, k={k}, fwd + bwd_input + bwd_skew + cnp_build",
+                               f"N={N} tokens, b={b}, k={k}, fwd + bwd_input + bwd_skew + cnp_build, {args.variant} variant",
                    "tokens_per_step": N, "block": b, "neumann_k": k},
         "mfma_peak_frac_layer": (dense_f + block_f + cnp_f) / (ms * 1e-3) / (PEAK_BF16_TFLOPS * 1e12),
         "algorithmic_tflop_per_step": (dense_f + block_f + cnp_f) / 1e12,

@@ -81,7 +81,15 @@ typedef struct {
   int64_t n_tokens;    /* N */
   int32_t dtype;       /* poetx_dtype of X, W, Z, saved B, gradients, blocks   */
   int32_t cnp_precision; /* poetx_cnp_precision used by poetx_linear_bwd_skew  */
+  int32_t flags;       /* POETX_FLAG_* bits                                    */
+  int32_t reserved;    /* must be 0                                            */
 } poetx_linear_desc;
+
+/* Memory-saving variant (Sec. 3.5, POET-X_mem): the forward pass keeps no activation
+ * (poetx_linear_fwd is called with saved_B = NULL and holds B in the workspace only) and the
+ * backward pass recomputes A = R^T X and B = W A with poetx_linear_recompute_b before
+ * poetx_linear_bwd_skew.  The flag sizes the workspace for that. */
+#define POETX_FLAG_RECOMPUTE_B 1
 
 const char* poetx_status_string(int status);
 
@@ -162,11 +170,18 @@ size_t poetx_linear_workspace_bytes(const poetx_linear_desc* desc);
 /* X: m x N.  W: n x m.  blocks_R / blocks_P: block storage of the dtype (see top)
  * with ceil(m/b) and ceil(n/b) blocks.
  * Z: n x N (out).  saved_B: n x N (out; the one activation the fast variant
- * keeps for the backward pass, physical feature order). */
+ * keeps for the backward pass, physical feature order).  saved_B may be NULL only
+ * when desc->flags has POETX_FLAG_RECOMPUTE_B. */
 int poetx_linear_fwd(const poetx_linear_desc* desc, const void* X, const void* W,
                      const int32_t* perm_R, const int32_t* perm_P,
                      const void* blocks_R, const void* blocks_P,
                      void* Z, void* saved_B, void* ws, size_t ws_bytes, void* stream);
+
+/* Gradient-checkpoint step of the memory-saving variant: B_out (n x N) = W (R^T X), the same
+ * values poetx_linear_fwd would have saved (same kernels, same rounding). */
+int poetx_linear_recompute_b(const poetx_linear_desc* desc, const void* X, const void* W,
+                             const int32_t* perm_R, const void* blocks_R, void* B_out,
+                             void* ws, size_t ws_bytes, void* stream);
 
 /* dZ: n x N.  dX: m x N (out).  dA: m x N (out; W^T P dZ in physical order,
  * consumed by poetx_linear_bwd_skew). */

@@ -17,12 +17,14 @@ LIB_PATH = os.path.join(_PKG, "libpoetx.so")
 
 F32, BF16 = 0, 1
 CNP_FP32, CNP_BF16 = 0, 1
+FLAG_RECOMPUTE_B = 1
 
 EXPORTS = (
     "poetx_status_string", "poetx_version", "poetx_debug_force_fma",
     "poetx_cnp_workspace_bytes", "poetx_cnp_build",
     "poetx_perm_blockdiag_apply_left", "poetx_perm_blockdiag_apply_right", "poetx_perm_validate",
     "poetx_linear_workspace_bytes", "poetx_linear_fwd", "poetx_linear_bwd_input", "poetx_linear_bwd_skew",
+    "poetx_linear_recompute_b",
     "poetx_profile_begin", "poetx_profile_end",
 )
 STAGES = ("cnp_fwd", "apply", "dense", "blockgrad", "cnp_bwd")
@@ -30,7 +32,8 @@ STAGES = ("cnp_fwd", "apply", "dense", "blockgrad", "cnp_bwd")
 
 class LinearDesc(Structure):
     _fields_ = [("d_in", c_int32), ("d_out", c_int32), ("block", c_int32), ("neumann_k", c_int32),
-                ("n_tokens", c_int64), ("dtype", c_int32), ("cnp_precision", c_int32)]
+                ("n_tokens", c_int64), ("dtype", c_int32), ("cnp_precision", c_int32),
+                ("flags", c_int32), ("reserved", c_int32)]
 
 
 class PoetxError(RuntimeError):
@@ -81,6 +84,8 @@ def load_library(path: str | None = None):
     lib.poetx_linear_bwd_skew.restype = c_int
     lib.poetx_linear_bwd_skew.argtypes = [POINTER(LinearDesc)] + [c_void_p] * 10 + [c_int32, c_void_p, c_size_t,
                                                                                    c_void_p]
+    lib.poetx_linear_recompute_b.restype = c_int
+    lib.poetx_linear_recompute_b.argtypes = [POINTER(LinearDesc)] + [c_void_p] * 6 + [c_size_t, c_void_p]
     lib.poetx_profile_begin.restype = c_int
     lib.poetx_profile_begin.argtypes = [c_int32]
     lib.poetx_profile_end.restype = c_int
@@ -123,10 +128,10 @@ def dtype_code(t) -> int:
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 
-def make_desc(d_in, d_out, block, neumann_k, n_tokens, dtype, cnp_precision=None) -> LinearDesc:
+def make_desc(d_in, d_out, block, neumann_k, n_tokens, dtype, cnp_precision=None, flags=0) -> LinearDesc:
     if cnp_precision is None:
         cnp_precision = CNP_FP32 if dtype == F32 else CNP_BF16
-    return LinearDesc(d_in, d_out, block, neumann_k, n_tokens, dtype, cnp_precision)
+    return LinearDesc(d_in, d_out, block, neumann_k, n_tokens, dtype, cnp_precision, flags, 0)
 
 
 def poetx_debug_force_fma(on: bool):
@@ -183,6 +188,13 @@ def poetx_linear_fwd(desc, X, W, perm_R, perm_P, blocks_R, blocks_P, Z, saved_B,
     _check(lib.poetx_linear_fwd(ctypes.byref(desc), _ptr(X), _ptr(W), _ptr(perm_R), _ptr(perm_P), _ptr(blocks_R),
                                 _ptr(blocks_P), _ptr(Z), _ptr(saved_B), _ptr(ws), _ws_bytes(ws), _stream()),
            "poetx_linear_fwd")
+
+
+def poetx_linear_recompute_b(desc, X, W, perm_R, blocks_R, B_out, ws):
+    lib = load_library()
+    _check(lib.poetx_linear_recompute_b(ctypes.byref(desc), _ptr(X), _ptr(W), _ptr(perm_R), _ptr(blocks_R), _ptr(B_out),
+                                        _ptr(ws), _ws_bytes(ws), _stream()),
+           "poetx_linear_recompute_b")
 
 
 def poetx_linear_bwd_input(desc, dZ, W, perm_R, perm_P, blocks_R, blocks_P, dX, dA, ws):

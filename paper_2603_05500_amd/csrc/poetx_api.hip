@@ -26,6 +26,7 @@ int check_desc(const poetx_linear_desc* d) {
     return POETX_ERR_INVALID_ARG;
   if (!dtype_ok(d->dtype)) return POETX_ERR_INVALID_ARG;
   if (d->cnp_precision != POETX_CNP_FP32 && d->cnp_precision != POETX_CNP_BF16) return POETX_ERR_INVALID_ARG;
+  if ((d->flags & ~POETX_FLAG_RECOMPUTE_B) != 0 || d->reserved != 0) return POETX_ERR_INVALID_ARG;
   if (d->block > d->d_in || d->block > d->d_out) return POETX_ERR_BAD_SHAPE;
   if (d->n_tokens >= (1ll << 31) || (i64)d->n_tokens * (d->d_in > d->d_out ? d->d_in : d->d_out) >= (1ll << 40))
     return POETX_ERR_UNSUPPORTED;
@@ -138,6 +139,7 @@ size_t poetx_linear_workspace_bytes(const poetx_linear_desc* desc) {
   size_t es = esize(desc->dtype);
   size_t N = (size_t)desc->n_tokens;
   size_t fwd = align256((size_t)desc->d_in * N * es);   // A = R^T X
+  if (desc->flags & POETX_FLAG_RECOMPUTE_B) fwd += align256((size_t)desc->d_out * N * es);  // B lives here too
   size_t bwi = align256((size_t)desc->d_out * N * es);  // dB = P dZ
   int dmax = desc->d_in > desc->d_out ? desc->d_in : desc->d_out;
   size_t bg_in = blockgrad_ws_bytes(desc->dtype, desc->d_in, desc->n_tokens, desc->block);
@@ -152,15 +154,31 @@ int poetx_linear_fwd(const poetx_linear_desc* desc, const void* X, const void* W
                      void* ws, size_t ws_bytes, void* stream) {
   int rc = check_desc(desc);
   if (rc) return rc;
-  if (!X || !W || !perm_R || !perm_P || !blocks_R || !blocks_P || !Z || !saved_B) return POETX_ERR_INVALID_ARG;
+  if (!X || !W || !perm_R || !perm_P || !blocks_R || !blocks_P || !Z) return POETX_ERR_INVALID_ARG;
+  if (!saved_B && !(desc->flags & POETX_FLAG_RECOMPUTE_B)) return POETX_ERR_INVALID_ARG;
   if (!ws || ws_bytes < poetx_linear_workspace_bytes(desc)) return POETX_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   const int m = desc->d_in, n = desc->d_out, b = desc->block, dt = desc->dtype;
   const i64 N = desc->n_tokens;
   void* A = ws;
+  if (!saved_B) saved_B = (char*)ws + align256((size_t)m * N * esize(dt));  // memory-saving variant: scratch only
   apply_left_dispatch(dt, X, A, m, N, N, perm_R, blocks_R, b, 1, st);        // mm1: A = R^T X
   dense_dispatch(dt, 0, W, n, m, A, saved_B, N, st);                        // mm2: B = W A
   apply_left_dispatch(dt, saved_B, Z, n, N, N, perm_P, blocks_P, b, 1, st);  // mm3: Z = P^T B
+  return launch_status();
+}
+
+int poetx_linear_recompute_b(const poetx_linear_desc* desc, const void* X, const void* W, const int32_t* perm_R,
+                             const void* blocks_R, void* B_out, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (!X || !W || !perm_R || !blocks_R || !B_out) return POETX_ERR_INVALID_ARG;
+  if (!ws || ws_bytes < poetx_linear_workspace_bytes(desc)) return POETX_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  const int m = desc->d_in, n = desc->d_out, b = desc->block, dt = desc->dtype;
+  const i64 N = desc->n_tokens;
+  apply_left_dispatch(dt, X, ws, m, N, N, perm_R, blocks_R, b, 1, st);  // A = R^T X
+  dense_dispatch(dt, 0, W, n, m, ws, B_out, N, st);                    // B = W A
   return launch_status();
 }
 

@@ -261,3 +261,33 @@ def test_merge_step(lib, m, n, b, dtype):
     assert rel_err(to_np(Wn), W_eff.T) <= TOL[dtype]
     # mergeability: plain product with the merged weight == POET-X forward with the factors
     assert rel_err(to_np(Wn) @ X, Zd) <= 2 * TOL[dtype]
+
+
+# ------------------------------------------------------------------ memory-saving variant
+@pytest.mark.parametrize("m,n,N,b,k,dtype", [(512, 256, 512, 256, 4, "bf16"), (256, 256, 512, 32, 4, "f32")])
+def test_mem_variant_matches_fast(lib, m, n, N, b, k, dtype):
+    """POET-X_mem: no saved activation in forward, B recomputed in backward -- same kernels, so the
+    outputs must equal the fast variant bit for bit (and the fast variant is checked against the oracle)."""
+    data = synth_layer(9500 + m + n, m, n, N, b, k, dtype)
+    fast = run_layer(data, dtype)
+    dev = fast["dev"]
+    code = lib.F32 if dtype == "f32" else lib.BF16
+    desc = lib.make_desc(m, n, b, k, N, code, flags=lib.FLAG_RECOMPUTE_B)
+    ws = ws_tensor(lib.poetx_linear_workspace_bytes(desc))
+    assert ws.numel() >= (m + n) * N * (4 if dtype == "f32" else 2)
+    Z = torch.empty_like(dev["Z"])
+    lib.poetx_linear_fwd(desc, dev["X"], dev["W"], dev["pi_R"], dev["pi_P"], dev["blk_R"], dev["blk_P"], Z, None, ws)
+    dX, dA = torch.empty_like(dev["dX"]), torch.empty_like(dev["dA"])
+    lib.poetx_linear_bwd_input(desc, dev["dZ"], dev["W"], dev["pi_R"], dev["pi_P"], dev["blk_R"], dev["blk_P"], dX, dA, ws)
+    B = torch.empty_like(dev["B"])
+    lib.poetx_linear_recompute_b(desc, dev["X"], dev["W"], dev["pi_R"], dev["blk_R"], B, ws)
+    dR, dP = torch.empty_like(dev["th_R"]), torch.empty_like(dev["th_P"])
+    lib.poetx_linear_bwd_skew(desc, dev["X"], dev["dZ"], B, dA, dev["pi_R"], dev["pi_P"], dev["th_R"], dev["th_P"],
+                              dR, dP, False, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(Z, dev["Z"]) and torch.equal(B, dev["B"]) and torch.equal(dX, dev["dX"])
+    assert np.array_equal(to_np(dR), fast["dtheta_R"]) and np.array_equal(to_np(dP), fast["dtheta_P"])
+    # without the flag a missing saved_B is refused on the host
+    with pytest.raises(lib.PoetxError):
+        lib.poetx_linear_fwd(dev["desc"], dev["X"], dev["W"], dev["pi_R"], dev["pi_P"], dev["blk_R"], dev["blk_P"],
+                             Z, None, dev["ws"])
