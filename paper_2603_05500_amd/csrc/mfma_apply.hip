@@ -131,62 +131,70 @@ __global__ __launch_bounds__(256) void apply_left_bf16_kernel(const uint16_t* __
 
 
 // ---------------------------------------------------------------------------------------
-// Streaming variant for b = 256: one persistent workgroup per (block, token range).
-//   * 8 waves; wave w owns block rows [32w, 32w+32) for loading, computing and storing.
-//   * op(E_j) rows of the wave stay in registers as matrix-core fragments for the whole range
-//     (16 k steps x 4 VGPRs), so the block operand is read once per workgroup.
-//   * token tiles of 128 go from HBM straight into a 2-stage LDS ring (global_load_lds, rows
-//     gathered through the permutation, XOR-swizzled chunks, no bank conflicts); the tile of
-//     the next step is in flight while the current one is multiplied.
+// Streaming variant: one persistent workgroup per (block, 256-row slice of it, token range).
+//   * 8 waves; wave w owns 32 output rows of the slice for computing and storing.
+//   * those rows of op(E_j) stay in registers as matrix-core fragments for the whole range
+//     (B/16 k steps x 4 VGPRs), so the block operand is read once per workgroup.
+//   * token tiles of BN go from HBM straight into a 2-stage LDS ring (global_load_lds, all B
+//     rows of the block gathered through the permutation, XOR-swizzled chunks, no bank
+//     conflicts); the tile of the next step is in flight while the current one is multiplied.
 //   * the identity part of G is applied as one exact extra MFMA per k step that covers the
 //     wave's own rows (1.0 * x accumulates exactly in fp32), so nothing is re-read.
 //   * results leave from registers: a lane owns one row and 4 consecutive tokens (8-byte
 //     packed stores), scattered through the same index map that gathered them.
-constexpr int SBN = 128;                      // tokens per tile
-constexpr int S_STAGE_BYTES = 256 * SBN * 2;  // 64 KB
-
-__global__ __launch_bounds__(512) void apply_left_stream256_kernel(const uint16_t* __restrict__ V,
-                                                                    uint16_t* __restrict__ out, i64 ld,
-                                                                    const int32_t* __restrict__ perm,
-                                                                    const uint16_t* __restrict__ blocks, int trans,
-                                                                    int tiles_per_wg) {
-  constexpr int B = 256, TN = SBN / 32, KS = B / 16;
+// b = 256: one slice, 128-token tiles.  b = 512: two slices per block (the block operand of
+// a whole block does not fit the register file), 64-token tiles; the two workgroups of a
+// block read the same token tiles, the second read being served by L2 / Infinity Cache.
+template <int B, int BN>
+__global__ __launch_bounds__(512) void apply_left_stream_kernel(const uint16_t* __restrict__ V,
+                                                                 uint16_t* __restrict__ out, i64 ld,
+                                                                 const int32_t* __restrict__ perm,
+                                                                 const uint16_t* __restrict__ blocks, int trans,
+                                                                 int tiles_per_wg) {
+  constexpr int MSPLIT = B / 256, TN = BN / 32, KS = B / 16;
+  constexpr int STAGE_BYTES = B * BN * 2;
+  constexpr int CPR = BN / 8;                        // 16-byte chunks per row
+  constexpr int RPI = 64 / CPR;                      // rows filled by one direct-to-LDS instruction
+  constexpr int IPW = STAGE_BYTES / 1024 / 8;        // such instructions per wave per stage
   extern __shared__ __attribute__((aligned(1024))) char ring[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int j = blockIdx.y;
-  const i64 tok0 = (i64)blockIdx.x * tiles_per_wg * SBN;
+  const int slice = blockIdx.x % MSPLIT;
+  const i64 tok0 = (i64)(blockIdx.x / MSPLIT) * tiles_per_wg * BN;
   const int32_t* pm = perm + (i64)j * B;
   const int li = lane & 31, h = lane >> 5;
   const uint32_t ring_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)ring;
 
-  // direct-to-LDS instruction s of this wave fills chunk slots [(8w+s)*64, +64) of a stage:
-  // row k = 32w + 4s + lane/16, chunk position lane%16 -> logical chunk through the swizzle.
-  i64 goff[8];
+  // direct-to-LDS instruction s of this wave fills chunk slots [(IPW*w+s)*64, +64) of a stage:
+  // row k = (IPW*w+s)*RPI + lane/CPR, chunk position lane%CPR -> logical chunk through the swizzle.
+  i64 goff[IPW];
 #pragma unroll
-  for (int s = 0; s < 8; ++s) {
-    const int k = wave * 32 + s * 4 + (lane >> 4);
-    const int c = mm::kx_unchunk<SBN>(lane & 15, k);
+  for (int s = 0; s < IPW; ++s) {
+    const int k = (wave * IPW + s) * RPI + lane / CPR;
+    const int c = mm::kx_unchunk<BN>(lane % CPR, k);
     goff[s] = (i64)pm[k] * ld + tok0 + c * 8;
   }
   auto issue = [&](int t) {
-    const uint32_t stage = ring_base + (t & 1) * S_STAGE_BYTES + wave * 8 * 1024;
+    const uint32_t stage = ring_base + (t & 1) * STAGE_BYTES + wave * IPW * 1024;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) mm::dma16(V + goff[s] + (i64)t * SBN, stage + s * 1024);
+    for (int s = 0; s < IPW; ++s) mm::dma16(V + goff[s] + (i64)t * BN, stage + s * 1024);
   };
   issue(0);
 
   // block operand fragments (rows of op(E_j) are contiguous in the stored pair)
-  const uint16_t* Eb = blocks + ((i64)j * 2 + (trans ? 1 : 0)) * B * B + (i64)(wave * 32 + li) * B + 8 * h;
+  const int row_own = slice * 256 + wave * 32 + li;
+  const uint16_t* Eb = blocks + ((i64)j * 2 + (trans ? 1 : 0)) * B * B + (i64)row_own * B + 8 * h;
   bf16x8 fa[KS];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) fa[ks] = *reinterpret_cast<const bf16x8*>(Eb + ks * 16);
-  // identity fragments for the two k steps that cover rows [32w, 32w+32)
+  // identity fragments for the two k steps that cover the wave's own 32 rows
   bf16x8 fi[2];
 #pragma unroll
   for (int u = 0; u < 2; ++u)
 #pragma unroll
     for (int e = 0; e < 8; ++e) fi[u][e] = (li == u * 16 + 8 * h + e) ? (__bf16)1.0f : (__bf16)0.0f;
+  const int own_kpair = slice * 8 + wave;  // k steps 2*own_kpair and 2*own_kpair + 1
 
   // LDS byte offsets of this lane's token fragments at k step 0
   int fragB[TN];
@@ -196,11 +204,11 @@ __global__ __launch_bounds__(512) void apply_left_stream256_kernel(const uint16_
 #pragma unroll
     for (int c2 = 0; c2 < TN; ++c2) {
       const int c = c2 * 4 + 2 * (q & 1) + ((i & 3) >> 1);
-      fragB[c2] = k * (SBN * 2) + 16 * mm::kx_chunk<SBN>(c, k) + 8 * (i & 1);
+      fragB[c2] = k * (BN * 2) + 16 * mm::kx_chunk<BN>(c, k) + 8 * (i & 1);
     }
   }
-  // store offsets: row 32w + li, tokens c*32 + 8q + 4h
-  const i64 soff = (i64)pm[wave * 32 + li] * ld + tok0 + 4 * h;
+  // store offsets: own row, tokens c*32 + 8q + 4h
+  const i64 soff = (i64)pm[row_own] * ld + tok0 + 4 * h;
 
   // The packed results of a tile are stored one iteration late, right after the next barrier:
   // by the following barrier both those stores and the loads of the next tile are old, so a
@@ -208,7 +216,7 @@ __global__ __launch_bounds__(512) void apply_left_stream256_kernel(const uint16_
   // one counter and may retire out of order with respect to each other).
   uint2 pend[TN * 4];
   auto flush = [&](int t) {
-    uint16_t* o = out + soff + (i64)t * SBN;
+    uint16_t* o = out + soff + (i64)t * BN;
 #pragma unroll
     for (int c = 0; c < TN; ++c)
 #pragma unroll
@@ -219,7 +227,7 @@ __global__ __launch_bounds__(512) void apply_left_stream256_kernel(const uint16_
     mm::wait_vmcnt_and_barrier<0>();
     if (t > 0) flush(t - 1);
     if (t + 1 < tiles_per_wg) issue(t + 1);
-    const char* stage = ring + (t & 1) * S_STAGE_BYTES;
+    const char* stage = ring + (t & 1) * STAGE_BYTES;
     floatx16 acc[TN];
 #pragma unroll
     for (int c = 0; c < TN; ++c)
@@ -230,15 +238,15 @@ __global__ __launch_bounds__(512) void apply_left_stream256_kernel(const uint16_
       bf16x8 fb[TN];
 #pragma unroll
       for (int c = 0; c < TN; ++c) {
-        const char* p = stage + fragB[c] + ks * 16 * (SBN * 2);
+        const char* p = stage + fragB[c] + ks * 16 * (BN * 2);
         short4v lo = mm::lds_read_tr(p);
-        short4v hi = mm::lds_read_tr(p + 4 * (SBN * 2));
+        short4v hi = mm::lds_read_tr(p + 4 * (BN * 2));
         short8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         fb[c] = __builtin_bit_cast(bf16x8, v);
       }
 #pragma unroll
       for (int c = 0; c < TN; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c], fa[ks], acc[c], 0, 0, 0);
-      if ((ks >> 1) == wave) {  // wave uniform: these 16 l values lie in the wave's own rows
+      if ((ks >> 1) == own_kpair) {  // wave uniform: these 16 l values lie in the wave's own rows
 #pragma unroll
         for (int c = 0; c < TN; ++c)
           acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c], fi[ks & 1], acc[c], 0, 0, 0);
@@ -255,34 +263,36 @@ __global__ __launch_bounds__(512) void apply_left_stream256_kernel(const uint16_
   flush(tiles_per_wg - 1);
 }
 
-// token ranges per block: fill the 256 CUs in whole rounds, at least 2 tiles per workgroup
-int stream_chunks(int nb, int tiles) {
+// token ranges per block slice: fill the 256 CUs in whole rounds, at least 2 tiles per workgroup
+int stream_chunks(int slices, int tiles) {
   int best = 1;
   double best_eff = 0.0;
   for (int c = 1; c <= tiles; c *= 2) {
     if (tiles % c != 0 || tiles / c < 2) break;
-    const double wgs = (double)nb * c;
-    const double rounds = (wgs + 255) / 256;
-    const double eff = wgs / 256.0 / (double)(long long)rounds;
+    const double wgs = (double)slices * c;
+    const double rounds = (double)(long long)((wgs + 255) / 256);
+    const double eff = wgs / 256.0 / rounds;
     if (eff > best_eff + 1e-9) { best_eff = eff; best = c; }
   }
   return best;
 }
 
-void launch_apply_stream256(const uint16_t* V, uint16_t* out, int d, i64 cols, i64 ld, const int32_t* perm,
-                            const uint16_t* E, int trans, hipStream_t st) {
-  constexpr size_t LDS = 2 * (size_t)S_STAGE_BYTES;
+template <int B, int BN>
+void launch_apply_stream(const uint16_t* V, uint16_t* out, int d, i64 cols, i64 ld, const int32_t* perm,
+                         const uint16_t* E, int trans, hipStream_t st) {
+  constexpr size_t LDS = 2 * (size_t)B * BN * 2;
+  constexpr int MSPLIT = B / 256;
+  auto kern = apply_left_stream_kernel<B, BN>;
   static bool configured = false;
   if (!configured) {
-    (void)hipFuncSetAttribute((const void*)apply_left_stream256_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)LDS);
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
     configured = true;
   }
-  const int nb = d / 256, tiles = (int)(cols / SBN);
-  const int chunks = stream_chunks(nb, tiles);
-  hipLaunchKernelGGL(apply_left_stream256_kernel, dim3(chunks, nb), dim3(512), LDS, st, V, out, ld, perm, E, trans,
-                     tiles / chunks);
+  const int nb = d / B, tiles = (int)(cols / BN);
+  const int chunks = stream_chunks(nb * MSPLIT, tiles);
+  hipLaunchKernelGGL(kern, dim3(chunks * MSPLIT, nb), dim3(512), LDS, st, V, out, ld, perm, E, trans, tiles / chunks);
 }
+constexpr int SBN256 = 128, SBN512 = 64;
 
 template <int B, int BN>
 void launch_apply(const uint16_t* V, uint16_t* out, int d, i64 cols, i64 ld, const int32_t* perm, const uint16_t* E,
@@ -310,8 +320,10 @@ bool mfma_apply_left_supported(int d, i64 cols, i64 ld, int b) {
 
 void mfma_apply_left(const void* V, void* out, int d, i64 cols, i64 ld, const int32_t* perm, const void* E, int b,
                      int transpose_G, hipStream_t st) {
-  if (b == 256 && cols % (2 * SBN) == 0)
-    launch_apply_stream256((const uint16_t*)V, (uint16_t*)out, d, cols, ld, perm, (const uint16_t*)E, transpose_G, st);
+  if (b == 256 && cols % (2 * SBN256) == 0)
+    launch_apply_stream<256, SBN256>((const uint16_t*)V, (uint16_t*)out, d, cols, ld, perm, (const uint16_t*)E, transpose_G, st);
+  else if (b == 512 && cols % (2 * SBN512) == 0)
+    launch_apply_stream<512, SBN512>((const uint16_t*)V, (uint16_t*)out, d, cols, ld, perm, (const uint16_t*)E, transpose_G, st);
   else if (b == 256)
     launch_apply<256, BN256>((const uint16_t*)V, (uint16_t*)out, d, cols, ld, perm, (const uint16_t*)E, transpose_G, st);
   else
