@@ -15,7 +15,9 @@ namespace poetx {
 namespace {
 
 // Small output tiles: one side has only a few blocks, so 64 x 64 tiles are what fills the 256 CUs.
-constexpr int CBM = 64, CBN = 64, CBK = 64;
+// A contraction is only b deep, so the latency of the first tiles is most of a launch: an
+// 8-deep ring puts six 8 KB tiles in flight at once (64 KB of LDS, two workgroups per CU).
+constexpr int CBM = 64, CBN = 64, CBK = 64, CNS = 8;
 
 __device__ inline float skew_at(const float* th, int i, int c, int b) {
   if (i == c) return 0.f;
@@ -143,7 +145,7 @@ void mfma_cnp_build(const float* theta, int d, int b, int k, float* G_f32, void*
     set_src(g.s[0], cur, Qb, b);
     uint16_t* nxt = H[step & 1];
     EpiHorner epi{Qf, 2.f, b, last ? nullptr : nxt, last ? G_f32 : nullptr, last ? (uint16_t*)E_bf16 : nullptr};
-    mm::launch<CBM, CBN, 2, 2, true, false, false>(g, epi, nb, 1, st);
+    mm::launch<CBM, CBN, 2, 2, true, false, false, CNS>(g, epi, nb, 1, st);
     cur = nxt;
   }
 }
@@ -177,7 +179,7 @@ void mfma_cnp_bwd(const float* theta, const float* dG, int d, int b, int k, floa
       set_src(g.alt[0], acur, Tb, b);
     }
     EpiBwdStep epi{dG, Qf, b, nb, last ? nullptr : Bb[ib], last ? Bfinal : nullptr, last ? nullptr : A[ia]};
-    mm::launch<CBM, CBN, 2, 2, true, false, false>(g, epi, last ? nb : 2 * nb, 1, st);
+    mm::launch<CBM, CBN, 2, 2, true, false, false, CNS>(g, epi, last ? nb : 2 * nb, 1, st);
     if (!last) {
       acur = A[ia];
       ia ^= 1;

@@ -4,8 +4,9 @@
 //   C[batch] (M x N) = sum over up to two sources s of  A_s[batch] * B_s[batch]
 //
 // Operand tiles go from global memory straight into LDS (global_load_lds, 16
-// bytes per lane, no staging registers) through a 4-deep ring of BK = 32 stages,
-// so three tiles are in flight while one is multiplied and the only per-tile
+// bytes per lane, no staging registers) through a ring of NS stages of BK = 32
+// (4 for the long contractions, deeper for the short ones of the series kernels),
+// so NS - 2 tiles are in flight while one is multiplied and the only per-tile
 // synchronisation is one barrier.  A tile is stored unpadded; bank conflicts are
 // avoided by an XOR swizzle of the 16-byte chunks, which costs nothing because
 // every lane may fetch any global chunk.
@@ -35,7 +36,6 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) short4v* lds_s4p;
 
 constexpr int BK = 32;       // contraction depth of one stage
-constexpr int NSTAGE = 4;    // ring depth
 
 __device__ inline short4v lds_read_tr(const char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4p)(p));
@@ -88,13 +88,14 @@ struct Args {
   int rows_per_batch;
 };
 
-template <int BM, int BN, int WGM, int WGN>
+// NS = ring depth (stages); NS - 2 tiles are in flight while one is multiplied.
+template <int BM, int BN, int WGM, int WGN, int NS>
 struct Cfg {
   static constexpr int NWAVE = WGM * WGN;
   static constexpr int A_BYTES = BM * BK * 2;
   static constexpr int B_BYTES = BN * BK * 2;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-  static constexpr size_t LDS_BYTES = (size_t)NSTAGE * STAGE_BYTES;
+  static constexpr size_t LDS_BYTES = (size_t)NS * STAGE_BYTES;
   static constexpr int IPW_A = A_BYTES / 1024 / NWAVE;   // direct-to-LDS instructions per wave per stage
   static constexpr int IPW_B = B_BYTES / 1024 / NWAVE;
   static_assert(IPW_A >= 1 && IPW_B >= 1, "tile too small for this many waves");
@@ -117,13 +118,31 @@ __device__ inline void wait_vmcnt_and_barrier() {
   asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
+// The same with a run-time (wave uniform) bound: at most min(tiles, MAXT) tiles of LPT loads
+// each may stay outstanding.  The count must be an immediate, hence the chain of cases.
+template <int LPT, int MAXT>
+__device__ inline void wait_tiles_and_barrier(int tiles) {
+  if constexpr (MAXT <= 0) {
+    wait_vmcnt_and_barrier<0>();
+  } else {
+    if (tiles >= MAXT) wait_vmcnt_and_barrier<MAXT * LPT>();
+    else wait_tiles_and_barrier<LPT, MAXT - 1>(tiles);
+  }
+}
+
 // Epi: __device__ void operator()(int batch, int split, int row, int col, float4 v) -- four
 // consecutive columns col..col+3 of output row `row` (indices local to the batch).
 // grid = (tiles_m * tiles_n, batches, splits).  With splits > 1 split z contracts k tiles
 // [z * ktiles, (z+1) * ktiles) of source 0.  Source::ktiles counts 64-deep tiles.
-template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, bool GATHER, class Epi>
+//
+// NS = 4 keeps the loop free of branches: loads past the last tile re-fetch it, so one fixed
+// vmcnt bound serves every iteration.  Deeper rings (short contractions, where the latency of
+// the first tiles is the whole cost) stop issuing after the last tile and shrink the bound.
+template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, bool GATHER, int NS, class Epi>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(Args g, Epi epi) {
-  using C = Cfg<BM, BN, WGM, WGN>;
+  using C = Cfg<BM, BN, WGM, WGN, NS>;
+  constexpr int NSTAGE = NS;
+  constexpr bool EXACT_TAIL = NS > 4;
   constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
 
@@ -286,17 +305,29 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(Args g, Epi e
   // so that its first fragments can be prefetched under the last MFMAs of tile kt), meets
   // the other waves, and refills the stage that tile kt-1 has just vacated.
   constexpr int LPT = C::IPW_A + C::IPW_B;  // direct-to-LDS loads per tile per wave
-  // Loads past the last tile re-fetch the last tile into a free stage: that keeps the
-  // number of outstanding loads constant, so the loop body has no branches and one
-  // fixed vmcnt threshold.
-  auto issue_clamped = [&](int t) { issue_at(t < KT ? t : KT - 1, t % NSTAGE); };
+  // NS = 4: loads past the last tile re-fetch the last tile into a free stage, which keeps
+  // the number of outstanding loads constant (no branches, one fixed vmcnt bound).
+  static_assert((NSTAGE - 1) * LPT < 64, "vmcnt range");
+  auto issue_clamped = [&](int t) {
+    if (EXACT_TAIL) {
+      if (t < KT) issue_at(t, t % NSTAGE);
+    } else {
+      issue_at(t < KT ? t : KT - 1, t % NSTAGE);
+    }
+  };
+  // tiles issued before tile t's turn at the top of the loop, and so the number of tiles
+  // younger than tile `need` that may still be in flight there
+  auto younger_than = [&](int issued_upto, int need) { return (issued_upto < KT ? issued_upto : KT) - 1 - need; };
 #pragma unroll
   for (int t = 0; t < NSTAGE - 1; ++t) issue_clamped(t);
-  wait_vmcnt_and_barrier<(NSTAGE - 2) * LPT>();
+  if (EXACT_TAIL) wait_tiles_and_barrier<LPT, NSTAGE - 2>(younger_than(NSTAGE - 1, 0));
+  else wait_vmcnt_and_barrier<(NSTAGE - 2) * LPT>();
   Frags F, G;
   load_frags(F, 0, 0);
   for (int kt = 0; kt < KT; ++kt) {
-    wait_vmcnt_and_barrier<(NSTAGE - 3) * LPT>();   // tile kt+1 has landed, for every wave
+    // tile kt+1 has landed, for every wave
+    if (EXACT_TAIL) wait_tiles_and_barrier<LPT, NSTAGE - 3>(younger_than(kt + NSTAGE - 1, kt + 1));
+    else wait_vmcnt_and_barrier<(NSTAGE - 3) * LPT>();
     issue_clamped(kt + NSTAGE - 1);                 // into the stage tile kt-1 vacated
     load_frags(G, kt, 1);
     mfma_all(F);
@@ -322,10 +353,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(Args g, Epi e
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, bool GATHER, class Epi>
+template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, bool GATHER, int NS = 4, class Epi>
 void launch(const Args& g, Epi epi, int batches, int splits, hipStream_t st) {
-  using C = Cfg<BM, BN, WGM, WGN>;
-  auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, A_KMAJOR, B_KMAJOR, GATHER, Epi>;
+  using C = Cfg<BM, BN, WGM, WGN, NS>;
+  auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, A_KMAJOR, B_KMAJOR, GATHER, NS, Epi>;
   static bool configured = false;
   if (!configured) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
