@@ -137,6 +137,10 @@ void mfma_cnp_build(const float* theta, int d, int b, int k, float* G_f32, void*
   uint16_t* H[2] = {Qb + total, Qb + 2 * total};
   hipLaunchKernelGGL(skew_materialize_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, theta, b, total, Qf, Qb,
                      (uint16_t*)nullptr);
+  if (lds_cnp_supported(d, b)) {   // whole chain in one launch, block resident in LDS
+    lds_cnp_build(Qf, Qb, d, k, G_f32, E_bf16, st);
+    return;
+  }
   const uint16_t* cur = Qb;  // H'_1 = Q
   for (int step = 0; step < k; ++step) {
     const bool last = step == k - 1;
@@ -154,6 +158,13 @@ void mfma_cnp_bwd(const float* theta, const float* dG, int d, int b, int k, floa
                   hipStream_t st) {
   const int nb = d / b;
   const i64 total = (i64)nb * b * b;
+  if (lds_cnp_supported(d, b)) {   // two launches, block resident in LDS; scratch = bf16(Q) + (k + 1) fp32 matrices
+    uint16_t* Qb = (uint16_t*)ws;
+    hipLaunchKernelGGL(skew_materialize_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, theta, b, total,
+                       (float*)nullptr, Qb, (uint16_t*)nullptr);
+    lds_cnp_bwd(Qb, dG, d, k, dtheta, accumulate, ws + total, st);
+    return;
+  }
   float* Qf = ws;
   float* Bfinal = Qf + total;
   uint16_t* Tb = (uint16_t*)(Bfinal + total);

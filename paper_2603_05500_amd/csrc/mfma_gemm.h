@@ -41,8 +41,12 @@ __device__ inline short4v lds_read_tr(const char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4p)(p));
 }
 
+// Two floats to two bf16 (round to nearest even) in one v_cvt_pk_bf16_f32; a in the low half.
 __device__ inline uint32_t pack2_bf16(float a, float b) {
-  return (uint32_t)float_to_bf16_bits(a) | ((uint32_t)float_to_bf16_bits(b) << 16);
+  typedef float float2v __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  const float2v f = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
 }
 
 // ---- swizzled tile layouts (16-byte chunk granularity) --------------------------------

@@ -33,8 +33,12 @@ int check_desc(const poetx_linear_desc* d) {
   return POETX_OK;
 }
 
-// dG plus chain scratch: five floats per block element cover both kernel families
-size_t cnp_bwd_ws_floats(int d, int b) { return (size_t)6 * ceil_div(d, b) * b * b; }
+// dG plus chain scratch per block element: five floats cover the tiled kernel families, the
+// on-chip chain keeps bf16(Q), k transposed terms and the result (k + 2 floats)
+size_t cnp_bwd_ws_floats(int d, int b, int k) {
+  const size_t per_elem = 1 + (size_t)(k + 2 > 5 ? k + 2 : 5);
+  return per_elem * ceil_div(d, b) * b * b;
+}
 
 void apply_left_dispatch(int dtype, const void* V, void* out, int d, i64 cols, i64 ld, const int32_t* perm,
                          const void* blocks, int b, int trans, hipStream_t st) {
@@ -144,7 +148,7 @@ size_t poetx_linear_workspace_bytes(const poetx_linear_desc* desc) {
   int dmax = desc->d_in > desc->d_out ? desc->d_in : desc->d_out;
   size_t bg_in = blockgrad_ws_bytes(desc->dtype, desc->d_in, desc->n_tokens, desc->block);
   size_t bg_out = blockgrad_ws_bytes(desc->dtype, desc->d_out, desc->n_tokens, desc->block);
-  size_t skew = align256(cnp_bwd_ws_floats(dmax, desc->block) * sizeof(float)) + (bg_in > bg_out ? bg_in : bg_out);
+  size_t skew = align256(cnp_bwd_ws_floats(dmax, desc->block, desc->neumann_k) * sizeof(float)) + (bg_in > bg_out ? bg_in : bg_out);
   size_t w = fwd > bwi ? fwd : bwi;
   return w > skew ? w : skew;
 }
@@ -214,7 +218,7 @@ int poetx_linear_bwd_skew(const poetx_linear_desc* desc, const void* X, const vo
   const int dmax = m > n ? m : n;
   float* dG = (float*)ws;
   float* chain = dG + (size_t)ceil_div(dmax, b) * b * b;
-  void* bg_ws = (char*)ws + align256(cnp_bwd_ws_floats(dmax, b) * sizeof(float));
+  void* bg_ws = (char*)ws + align256(cnp_bwd_ws_floats(dmax, b, k) * sizeof(float));
   for (int side = 0; side < 2; ++side) {
     const void* U = side == 0 ? saved_B : X;   // mm3 backward: dG_P = B' dZ'^T; mm1 backward: dG_R = X' dA'^T
     const void* V = side == 0 ? dZ : dA;

@@ -56,5 +56,11 @@ void mfma_cnp_build(const float* theta, int d, int b, int k, float* G_f32, void*
                     hipStream_t st);
 void mfma_cnp_bwd(const float* theta, const float* dG, int d, int b, int k, float* dtheta, int accumulate,
                   float* ws, hipStream_t st);
+// b = 256: whole chain of a block in one launch, block resident in LDS (mfma_cnp_lds.hip).
+// Qf / Qb: Q in fp32 / bf16, [nb][b][b].  The backward needs (k + 1) * nb*b*b floats of scratch.
+bool lds_cnp_supported(int d, int b);
+void lds_cnp_build(const float* Qf, const uint16_t* Qb, int d, int k, float* G_f32, void* E_bf16, hipStream_t st);
+void lds_cnp_bwd(const uint16_t* Qb, const float* dG, int d, int k, float* dtheta, int accumulate, float* ws,
+                 hipStream_t st);
 
 }  // namespace poetx

@@ -25,7 +25,7 @@ def pair(E):
 
 # ------------------------------------------------------------------ cnp_build
 @pytest.mark.parametrize("d,b,k", [(64, 32, 3), (256, 32, 4), (96, 64, 4), (1376, 64, 4), (512, 256, 5),
-                                   (1024, 512, 5), (40, 8, 1), (48, 16, 2)])
+                                   (1024, 512, 5), (40, 8, 1), (48, 16, 2), (256, 256, 1), (768, 256, 2), (1024, 256, 3)])
 @pytest.mark.parametrize("precision", ["fp32", "bf16"])
 def test_cnp_build(lib, d, b, k, precision):
     rng = RNG(1000 + d + b + k)
@@ -232,6 +232,20 @@ def test_bf16_layer_matrix_core_shapes(lib, m, n, N, b, k):
     finally:
         lib.poetx_debug_force_fma(False)
     check_layer(res2, ref, data["pi_P"], "bf16")
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 6])
+def test_on_chip_series_orders(lib, k):
+    """b = 256 runs the series and its backward as one-launch chains with the block resident on
+    chip; the chain length is a run-time loop, so every order takes its own path through it
+    (k = 1: no intermediate step at all).  theta is drawn larger than in the workloads so
+    that the high-order terms are well above the bf16 noise of the low-order ones."""
+    m, n, N, b = 256, 512, 256, 256
+    data = synth_layer(7300 + k, m, n, N, b, k, "bf16", 0.01)
+    ref = orc.linear_fwd_bwd_from_theta(data["X"], data["dZ"], data["W"], data["pi_R"], data["pi_P"],
+                                        data["theta_R"], data["theta_P"], b, k)
+    res = run_layer(data, "bf16")
+    check_layer(res, ref, data["pi_P"], "bf16")
 
 
 # ------------------------------------------------------------------ merge step W <- R W P
