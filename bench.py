@@ -31,7 +31,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama8b-b256",
-                    help="llama8b-b256 (default, the metric's configuration), llama8b-b512, llama3b, llama1b")
+                    help="llama8b-b256 (default, the metric's configuration), llama8b-b512, llama3b (fresh "
+                         "permutations every step), llama1b; or `micro`: the shapes of the paper's kernel tables "
+                         "(permutation, block-diagonal product, Cayley-Neumann build) on the library's entry points")
     ap.add_argument("--variant", default="fast", choices=["fast", "mem"],
                     help="fast keeps B from the forward pass (the measured metric); mem recomputes it in backward")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -44,7 +46,7 @@ def parse():
 
 def layer_flops(cfg):
     """Algorithmic flops of one step: two dense products, six block products per side,
-    and the series (k products forward, 3k-1 backward per block)."""
+    and the series (k products forward, 2k backward per block)."""
     N, b, k = cfg.n_tokens, cfg.block, cfg.neumann_k
     dense = block = cnp = 0.0
     for p in cfg.projections:
@@ -52,7 +54,7 @@ def layer_flops(cfg):
         dense += 4.0 * N * m * n
         block += 6.0 * N * (m + n) * b
         nb = -(-m // b) + -(-n // b)
-        cnp += nb * (k + 3 * k - 1) * 2.0 * b ** 3
+        cnp += nb * (k + 2 * k) * 2.0 * b ** 3
     return dense, block, cnp
 
 
@@ -73,7 +75,12 @@ def make_inputs(cfg, torch):
             nb = -(-dim // b)
             d["theta_" + side] = torch.randn((nb, b * (b - 1) // 2), generator=g, device="cuda",
                                              dtype=torch.float32) * cfg.sigma_theta
-            d["pi_" + side] = torch.randperm(dim, generator=g, device="cuda").to(torch.int32)
+            # fresh permutations per step (Sec. 3, merge-and-resample): a pool of index vectors made
+            # before the timed region, walked round robin; permutations are inputs of every call, so a new
+            # one costs the path nothing
+            npool = 4 if cfg.fresh_perms else 1
+            d["pool_" + side] = [torch.randperm(dim, generator=g, device="cuda").to(torch.int32) for _ in range(npool)]
+            d["pi_" + side] = d["pool_" + side][0]
             shape = (nb, 2, b, b) if cfg.dtype == "bf16" else (nb, b, b)  # bf16: (G - I, its transpose)
             d["blk_" + side] = torch.empty(shape, device="cuda", dtype=dt)
             d["dtheta_" + side] = torch.empty_like(d["theta_" + side])
@@ -120,6 +127,55 @@ def cpu_baseline(cfg, n_tok):
                       f"series build/backward {t_cnp:.2f}s counted once"}
 
 
+def time_call(torch, fn, iters, warm=3):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def micro(args, torch, px):
+    """The shapes of the paper's kernel tables on this library's entry points (bf16, b = 256 unless
+    said): permutation + block-diagonal product fused (apply_left) over hidden sizes and over
+    token counts, and the Cayley-Neumann build at k = 3 over block counts.  The paper does not
+    state batch / sequence for its tables, so the token counts here are this build's choice."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(20260305)
+    it = max(args.steps, 5)
+    out = {"apply_vs_hidden": [], "apply_vs_tokens": [], "cnp_build_k3": []}
+    b = 256
+
+    def apply_case(d, N):
+        V = torch.randn((d, N), generator=g, device="cuda").to(torch.bfloat16)
+        O = torch.empty_like(V)
+        E = (torch.randn((d // b, 2, b, b), generator=g, device="cuda") * 0.01).to(torch.bfloat16)
+        perm = torch.randperm(d, generator=g, device="cuda").to(torch.int32)
+        ms = time_call(torch, lambda: px.poetx_perm_blockdiag_apply_left(V, O, perm, E, b, True), it)
+        return {"hidden": d, "tokens": N, "ms": ms, "GBs": 4.0 * d * N / ms / 1e6}
+
+    for d in (2048, 4096, 8192, 16384):      # permutation table: hidden size sweep
+        out["apply_vs_hidden"].append(apply_case(d, 8192))
+    for N in (2048, 4096, 8192, 16384):      # block-diagonal table: sequence length sweep
+        out["apply_vs_tokens"].append(apply_case(4096, N))
+    for bb in (256, 512):                    # Cayley-Neumann table: number of blocks sweep, k = 3
+        for nb in (64, 128, 192, 256, 320):
+            d = nb * bb
+            theta = torch.randn((nb, bb * (bb - 1) // 2), generator=g, device="cuda") * 0.005
+            E = torch.empty((nb, 2, bb, bb), device="cuda", dtype=torch.bfloat16)
+            ws = torch.empty(px.poetx_cnp_workspace_bytes(d, bb), dtype=torch.uint8, device="cuda")
+            ms = time_call(torch, lambda: px.poetx_cnp_build(theta, d, bb, 3, px.CNP_BF16, E_bf16=E, ws=ws), it)
+            out["cnp_build_k3"].append({"block": bb, "blocks": nb, "ms": ms,
+                                        "TFLOPs": nb * 3 * 2.0 * bb ** 3 / ms / 1e9})
+            del theta, E, ws
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -130,6 +186,15 @@ def main():
     from workloads import get_config
 
     px.load_library()
+    if args.workload == "micro":
+        torch.cuda.set_device(0)
+        res = micro(args, torch, px)
+        print(json.dumps({"metric": "POET-X kernel microbenchmarks at the shapes of the paper's kernel tables",
+                          "unit": "ms", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": "micro: fused permutation + block-diagonal apply (b=256) over hidden "
+                                                 "size and token count; Cayley-Neumann build k=3 over block count"},
+                          "micro": res}))
+        return
     cfg = get_config(args.workload)
     torch.cuda.set_device(0)
     code = px.BF16 if cfg.dtype == "bf16" else px.F32
@@ -152,9 +217,13 @@ def main():
     cws = torch.empty(cnp_bytes, dtype=torch.uint8, device="cuda")
     prec = px.CNP_BF16 if code == px.BF16 else px.CNP_FP32
 
+    step_no = [0]
+
     def step():
         for p in projs:
             m, n = p["m"], p["n"]
+            p["pi_R"] = p["pool_R"][step_no[0] % len(p["pool_R"])]
+            p["pi_P"] = p["pool_P"][step_no[0] % len(p["pool_P"])]
             kw = {"E_bf16": p["blk_R"]} if code == px.BF16 else {"G_f32": p["blk_R"]}
             px.poetx_cnp_build(p["theta_R"], m, b, k, prec, ws=cws, **kw)
             kw = {"E_bf16": p["blk_P"]} if code == px.BF16 else {"G_f32": p["blk_P"]}
@@ -167,6 +236,7 @@ def main():
                 px.poetx_linear_recompute_b(p["desc"], p["X"], p["W"], p["pi_R"], p["blk_R"], B[:n], ws)
             px.poetx_linear_bwd_skew(p["desc"], p["X"], p["dZ"], B[:n], dA[:m], p["pi_R"], p["pi_P"],
                                      p["theta_R"], p["theta_P"], p["dtheta_R"], p["dtheta_P"], False, ws)
+        step_no[0] += 1
 
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB
@@ -207,7 +277,8 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: one decoder layer = 7 POET-X linears "
                                f"({', '.join(f'{p.name} {p.d_out}x{p.d_in}' for p in cfg.projections)}), "
-                               f"N={N} tokens, b={b}, k={k}, fwd + bwd_input + bwd_skew + cnp_build, {args.variant} variant",
+                               f"N={N} tokens, b={b}, k={k}, fwd + bwd_input + bwd_skew + cnp_build, {args.variant} variant"
+                               + (", a fresh permutation pair per projection every step" if cfg.fresh_perms else ""),
                    "tokens_per_step": N, "block": b, "neumann_k": k},
         "mfma_peak_frac_layer": (dense_f + block_f + cnp_f) / (ms * 1e-3) / (PEAK_BF16_TFLOPS * 1e12),
         "algorithmic_tflop_per_step": (dense_f + block_f + cnp_f) / 1e12,
