@@ -32,6 +32,10 @@ Pin status (see tests/test_oracle_pins.py): every function below is pinned by
 dense materialisation, closed forms of the Cayley transform, the orthogonality
 defect identity, singular-value preservation, or central finite differences.
 The paper prints no worked numerical example, so no stored paper values exist.
+``weight_quantize_q8`` / ``weight_dequantize_q8`` (Sec. 3.6): the paper does not
+state its quantisation scheme, so the scheme is this build's reading and is
+"parity unpinned" against the paper; the routines are pinned to that reading's
+own definition (error bound, code range, exact round trips, idempotence).
 """
 from __future__ import annotations
 
@@ -332,3 +336,27 @@ def linear_fwd_bwd_from_theta(X, dZ, W, pi_R, pi_P, theta_R, theta_P, b, k):
     return {"G_R": G_R, "G_P": G_P, "Z": f["Z"], "Bp": f["Bp"], "Ap": f["Ap"],
             "dX": g["dX"], "dG_R": g["dG_R"], "dG_P": g["dG_P"], "dAp": g["dAp"],
             "dBp": g["dBp"], "dtheta_R": dth_R, "dtheta_P": dth_P}
+
+
+# --------------------------------------------------------------------------
+# POET-XQ  (Sec. 3.6: the frozen base weight is stored in INT8 and dequantised
+# whenever it is needed).  The paper does not give the scheme; this reading:
+# symmetric absmax per output row,  s_i = max_k |W[i,k]| / 127  (1 for a zero
+# row),  q[i,k] = round-half-even(W[i,k] / s_i) clamped to [-127, 127],
+# W[i,k] ~ s_i q[i,k].  The scale and the rounding decision are taken in fp32,
+# the precision the device uses, so that the integer codes are comparable bit
+# for bit; everything downstream of the codes is fp64.
+# --------------------------------------------------------------------------
+def weight_quantize_q8(W: np.ndarray):
+    """W (n x m, values already in the storage dtype) -> (q int8 n x m, scale float32 n)."""
+    W32 = np.asarray(W, dtype=np.float32)
+    amax = np.max(np.abs(W32), axis=1)
+    scale = np.where(amax > 0, amax / np.float32(127.0), np.float32(1.0)).astype(np.float32)
+    q = np.rint(W32 / scale[:, None])          # fp32 division, round half to even
+    q = np.clip(q, -127.0, 127.0).astype(np.int8)
+    return q, scale
+
+
+def weight_dequantize_q8(q: np.ndarray, scale: np.ndarray) -> np.ndarray:
+    """(q, scale) -> the weight the layer multiplies by, fp64 n x m: s_i * q[i,k] exactly."""
+    return np.asarray(scale, dtype=F64)[:, None] * np.asarray(q, dtype=F64)

@@ -306,3 +306,46 @@ def test_packed_grad_is_skew_projection():
     # directional check: <dQ, skew(t)> = <dtheta, t>
     t = rng.standard_normal((2, b * (b - 1) // 2))
     assert np.sum(dQ * orc.skew_from_packed(t, b)) == pytest.approx(np.sum(dth * t), rel=1e-12)
+
+
+# ------------------------------------------------------------------ POET-XQ weight codes (Sec. 3.6, this build's reading)
+def test_q8_error_bound_range_and_zero_rows():
+    rng = np.random.Generator(np.random.PCG64(811))
+    W = rng.standard_normal((37, 129)) * 0.02
+    W[5] = 0.0
+    W[9, :] = 0.0
+    W[9, 17] = -0.3                      # a single non-zero: it must become code -127 exactly
+    q, s = orc.weight_quantize_q8(W)
+    assert q.dtype == np.int8 and s.dtype == np.float32 and q.shape == W.shape and s.shape == (37,)
+    assert q.min() >= -127 and q.max() <= 127
+    assert s[5] == 1.0 and not q[5].any()
+    assert q[9, 17] == -127 and np.count_nonzero(q[9]) == 1
+    # every row attains +-127 at its absolute maximum
+    assert np.all(np.max(np.abs(q.astype(int)), axis=1)[np.abs(W).max(axis=1) > 0] == 127)
+    # rounding to the nearest code: error at most half a step (plus fp32 slack on the quotient)
+    err = np.abs(orc.weight_dequantize_q8(q, s) - W.astype(np.float32))
+    assert np.all(err <= 0.5 * s[:, None].astype(np.float64) * (1 + 1e-6))
+
+
+def test_q8_exact_roundtrip_and_idempotence():
+    rng = np.random.Generator(np.random.PCG64(812))
+    codes = rng.integers(-127, 128, size=(16, 64)).astype(np.int8)
+    codes[:, 0] = 127                    # fix the row maximum so that the scale is recovered
+    scale = (2.0 ** rng.integers(-12, -4, size=16)).astype(np.float32)   # powers of two: products exact
+    W = orc.weight_dequantize_q8(codes, scale)
+    q, s = orc.weight_quantize_q8(W)
+    assert np.array_equal(q, codes) and np.array_equal(s, scale)
+    # quantising a dequantised weight changes nothing
+    W2 = rng.standard_normal((8, 50))
+    q1, s1 = orc.weight_quantize_q8(W2)
+    q2, s2 = orc.weight_quantize_q8(orc.weight_dequantize_q8(q1, s1).astype(np.float32))
+    assert np.array_equal(q1, q2)
+    assert np.allclose(s1, s2, rtol=1e-6)
+
+
+def test_q8_half_steps_round_to_even():
+    s = np.float32(2.0 ** -7)
+    row = np.array([127, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 126.5], dtype=np.float64) * float(s)
+    q, sc = orc.weight_quantize_q8(row[None, :])
+    assert sc[0] == s
+    assert q[0].tolist() == [127, 0, 2, 2, 0, -2, -2, 126]
