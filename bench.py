@@ -34,8 +34,9 @@ def parse():
                     help="llama8b-b256 (default, the metric's configuration), llama8b-b512, llama3b (fresh "
                          "permutations every step), llama1b; or `micro`: the shapes of the paper's kernel tables "
                          "(permutation, block-diagonal product, Cayley-Neumann build) on the library's entry points")
-    ap.add_argument("--variant", default="fast", choices=["fast", "mem"],
-                    help="fast keeps B from the forward pass (the measured metric); mem recomputes it in backward")
+    ap.add_argument("--variant", default="fast", choices=["fast", "mem", "xq"],
+                    help="fast keeps B from the forward pass (the measured metric); mem recomputes it in backward; "
+                         "xq is mem on an INT8 base weight that every dense product dequantises first")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=128, help="tokens in the oracle's timed sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -209,8 +210,13 @@ def main():
     dA = torch.empty((mmax, N), device="cuda", dtype=dt)
     ws_bytes = cnp_bytes = 0
     for p in projs:
-        p["desc"] = px.make_desc(p["m"], p["n"], b, k, N, code,
-                                 flags=px.FLAG_RECOMPUTE_B if args.variant == "mem" else 0)
+        flags = {"fast": 0, "mem": px.FLAG_RECOMPUTE_B, "xq": px.FLAG_RECOMPUTE_B | px.FLAG_W_INT8}[args.variant]
+        p["desc"] = px.make_desc(p["m"], p["n"], b, k, N, code, flags=flags)
+        if args.variant == "xq":   # only the 8-bit weight stays resident
+            wq = torch.zeros(px.poetx_weight_q8_bytes(p["n"], p["m"]), dtype=torch.uint8, device="cuda")
+            px.poetx_weight_quantize_q8(p["W"], wq)
+            torch.cuda.synchronize()
+            p["W"] = wq
         ws_bytes = max(ws_bytes, px.poetx_linear_workspace_bytes(p["desc"]))
         cnp_bytes = max(cnp_bytes, px.poetx_cnp_workspace_bytes(max(p["m"], p["n"]), b))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
@@ -229,10 +235,10 @@ def main():
             kw = {"E_bf16": p["blk_P"]} if code == px.BF16 else {"G_f32": p["blk_P"]}
             px.poetx_cnp_build(p["theta_P"], n, b, k, prec, ws=cws, **kw)
             px.poetx_linear_fwd(p["desc"], p["X"], p["W"], p["pi_R"], p["pi_P"], p["blk_R"], p["blk_P"],
-                                Z[:n], None if args.variant == "mem" else B[:n], ws)
+                                Z[:n], None if args.variant != "fast" else B[:n], ws)
             px.poetx_linear_bwd_input(p["desc"], p["dZ"], p["W"], p["pi_R"], p["pi_P"], p["blk_R"], p["blk_P"],
                                       dX[:m], dA[:m], ws)
-            if args.variant == "mem":
+            if args.variant != "fast":
                 px.poetx_linear_recompute_b(p["desc"], p["X"], p["W"], p["pi_R"], p["blk_R"], B[:n], ws)
             px.poetx_linear_bwd_skew(p["desc"], p["X"], p["dZ"], B[:n], dA[:m], p["pi_R"], p["pi_P"],
                                      p["theta_R"], p["theta_P"], p["dtheta_R"], p["dtheta_P"], False, ws)

@@ -91,6 +91,21 @@ typedef struct {
  * poetx_linear_bwd_skew.  The flag sizes the workspace for that. */
 #define POETX_FLAG_RECOMPUTE_B 1
 
+/* Quantised base weight (Sec. 3.6, POET-XQ): the frozen W is stored as signed 8-bit codes and
+ * dequantised whenever it is needed, so no high-precision weight persists.  The paper does not
+ * state its quantisation scheme; this library uses symmetric absmax codes per output row:
+ *   scale_i = max_k |W[i][k]| / 127 (1 for an all-zero row),
+ *   q[i][k] = round-half-even(W[i][k] / scale_i) clamped to [-127, 127]   (decided in fp32),
+ *   W[i][k] ~ scale_i * q[i][k].
+ * A quantised weight buffer is int8 q[n][m] row major followed, at byte offset
+ * (n*m rounded up to 256), by float scale[n]; poetx_weight_q8_bytes gives its size.
+ * With this flag the W argument of poetx_linear_fwd, poetx_linear_recompute_b and
+ * poetx_linear_bwd_input is such a buffer: each call dequantises it into the workspace in the
+ * layer's dtype right before its dense product and keeps nothing.  As in the paper the flag
+ * is only valid together with POETX_FLAG_RECOMPUTE_B (the variant that keeps no activation);
+ * alone it is POETX_ERR_INVALID_ARG.  The flag enlarges the workspace by one n x m weight. */
+#define POETX_FLAG_W_INT8 2
+
 const char* poetx_status_string(int status);
 
 /* Library version (major * 100 + minor). */
@@ -133,6 +148,15 @@ int poetx_cnp_build(const float* theta, int32_t d, int32_t b, int32_t k, int32_t
                     float* G_f32, void* E_bf16, void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * INT8 codes of a base weight (Sec. 3.6; scheme and buffer layout: see POETX_FLAG_W_INT8).
+ * W: n x m in `dtype`.  Wq: poetx_weight_q8_bytes(n, m) bytes (out of quantize, in of
+ * dequantize).  W_out: n x m in `dtype`, scale_i * q[i][k] rounded once to that type.
+ */
+size_t poetx_weight_q8_bytes(int32_t n, int32_t m);
+int poetx_weight_quantize_q8(const void* W, int32_t dtype, int32_t n, int32_t m, void* Wq, void* stream);
+int poetx_weight_dequantize_q8(const void* Wq, int32_t n, int32_t m, int32_t dtype, void* W_out, void* stream);
+
+/* ---------------------------------------------------------------------------
  * Structured apply without materialising the orthogonal matrix (Eq. 2 with
  * Eq. 5 and Eq. 7):
  *   left :  out = Psi^T Diag(op(G)) Psi * V,   V and out are d x cols, leading
@@ -171,7 +195,8 @@ size_t poetx_linear_workspace_bytes(const poetx_linear_desc* desc);
  * with ceil(m/b) and ceil(n/b) blocks.
  * Z: n x N (out).  saved_B: n x N (out; the one activation the fast variant
  * keeps for the backward pass, physical feature order).  saved_B may be NULL only
- * when desc->flags has POETX_FLAG_RECOMPUTE_B. */
+ * when desc->flags has POETX_FLAG_RECOMPUTE_B.  With POETX_FLAG_W_INT8, W is a quantised
+ * weight buffer (also in poetx_linear_recompute_b and poetx_linear_bwd_input). */
 int poetx_linear_fwd(const poetx_linear_desc* desc, const void* X, const void* W,
                      const int32_t* perm_R, const int32_t* perm_P,
                      const void* blocks_R, const void* blocks_P,

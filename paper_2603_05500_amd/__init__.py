@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libpoetx.so")
 F32, BF16 = 0, 1
 CNP_FP32, CNP_BF16 = 0, 1
 FLAG_RECOMPUTE_B = 1
+FLAG_W_INT8 = 2
 
 EXPORTS = (
     "poetx_status_string", "poetx_version", "poetx_debug_force_fma",
@@ -25,6 +26,7 @@ EXPORTS = (
     "poetx_perm_blockdiag_apply_left", "poetx_perm_blockdiag_apply_right", "poetx_perm_validate",
     "poetx_linear_workspace_bytes", "poetx_linear_fwd", "poetx_linear_bwd_input", "poetx_linear_bwd_skew",
     "poetx_linear_recompute_b",
+    "poetx_weight_q8_bytes", "poetx_weight_quantize_q8", "poetx_weight_dequantize_q8",
     "poetx_profile_begin", "poetx_profile_end",
 )
 STAGES = ("cnp_fwd", "apply", "dense", "blockgrad", "cnp_bwd")
@@ -86,6 +88,12 @@ def load_library(path: str | None = None):
                                                                                    c_void_p]
     lib.poetx_linear_recompute_b.restype = c_int
     lib.poetx_linear_recompute_b.argtypes = [POINTER(LinearDesc)] + [c_void_p] * 6 + [c_size_t, c_void_p]
+    lib.poetx_weight_q8_bytes.restype = c_size_t
+    lib.poetx_weight_q8_bytes.argtypes = [c_int32, c_int32]
+    lib.poetx_weight_quantize_q8.restype = c_int
+    lib.poetx_weight_quantize_q8.argtypes = [c_void_p, c_int32, c_int32, c_int32, c_void_p, c_void_p]
+    lib.poetx_weight_dequantize_q8.restype = c_int
+    lib.poetx_weight_dequantize_q8.argtypes = [c_void_p, c_int32, c_int32, c_int32, c_void_p, c_void_p]
     lib.poetx_profile_begin.restype = c_int
     lib.poetx_profile_begin.argtypes = [c_int32]
     lib.poetx_profile_end.restype = c_int
@@ -212,6 +220,23 @@ def poetx_linear_bwd_skew(desc, X, dZ, saved_B, dA, perm_R, perm_P, theta_R, the
                                      _ptr(perm_P), _ptr(theta_R), _ptr(theta_P), _ptr(dtheta_R), _ptr(dtheta_P),
                                      int(bool(accumulate)), _ptr(ws), _ws_bytes(ws), _stream()),
            "poetx_linear_bwd_skew")
+
+
+def poetx_weight_q8_bytes(n: int, m: int) -> int:
+    return load_library().poetx_weight_q8_bytes(n, m)
+
+
+def poetx_weight_quantize_q8(W, Wq):
+    """W: n x m tensor (f32 or bf16) -> Wq: uint8/int8 buffer of poetx_weight_q8_bytes(n, m) bytes."""
+    n, m = W.shape
+    _check(load_library().poetx_weight_quantize_q8(_ptr(W), dtype_code(W), n, m, _ptr(Wq), _stream()),
+           "poetx_weight_quantize_q8")
+
+
+def poetx_weight_dequantize_q8(Wq, W_out):
+    n, m = W_out.shape
+    _check(load_library().poetx_weight_dequantize_q8(_ptr(Wq), n, m, dtype_code(W_out), _ptr(W_out), _stream()),
+           "poetx_weight_dequantize_q8")
 
 
 def poetx_profile_begin(max_records: int = 65536):

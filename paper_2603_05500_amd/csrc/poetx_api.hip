@@ -26,7 +26,8 @@ int check_desc(const poetx_linear_desc* d) {
     return POETX_ERR_INVALID_ARG;
   if (!dtype_ok(d->dtype)) return POETX_ERR_INVALID_ARG;
   if (d->cnp_precision != POETX_CNP_FP32 && d->cnp_precision != POETX_CNP_BF16) return POETX_ERR_INVALID_ARG;
-  if ((d->flags & ~POETX_FLAG_RECOMPUTE_B) != 0 || d->reserved != 0) return POETX_ERR_INVALID_ARG;
+  if ((d->flags & ~(POETX_FLAG_RECOMPUTE_B | POETX_FLAG_W_INT8)) != 0 || d->reserved != 0) return POETX_ERR_INVALID_ARG;
+  if ((d->flags & POETX_FLAG_W_INT8) && !(d->flags & POETX_FLAG_RECOMPUTE_B)) return POETX_ERR_INVALID_ARG;
   if (d->block > d->d_in || d->block > d->d_out) return POETX_ERR_BAD_SHAPE;
   if (d->n_tokens >= (1ll << 31) || (i64)d->n_tokens * (d->d_in > d->d_out ? d->d_in : d->d_out) >= (1ll << 40))
     return POETX_ERR_UNSUPPORTED;
@@ -103,6 +104,23 @@ int poetx_cnp_build(const float* theta, int32_t d, int32_t b, int32_t k, int32_t
   return launch_status();
 }
 
+size_t poetx_weight_q8_bytes(int32_t n, int32_t m) {
+  if (n <= 0 || m <= 0) return 0;
+  return weight_q8_scale_offset(n, m) + align256((size_t)n * sizeof(float));
+}
+
+int poetx_weight_quantize_q8(const void* W, int32_t dtype, int32_t n, int32_t m, void* Wq, void* stream) {
+  if (!W || !Wq || n <= 0 || m <= 0 || !dtype_ok(dtype)) return POETX_ERR_INVALID_ARG;
+  weight_quantize_q8_launch(dtype, W, n, m, Wq, (hipStream_t)stream);
+  return launch_status();
+}
+
+int poetx_weight_dequantize_q8(const void* Wq, int32_t n, int32_t m, int32_t dtype, void* W_out, void* stream) {
+  if (!Wq || !W_out || n <= 0 || m <= 0 || !dtype_ok(dtype)) return POETX_ERR_INVALID_ARG;
+  weight_dequantize_q8_launch(Wq, n, m, dtype, W_out, (hipStream_t)stream);
+  return launch_status();
+}
+
 int poetx_perm_blockdiag_apply_left(const void* V, void* out, int32_t d, int64_t cols, int64_t ld,
                                     const int32_t* perm, const void* blocks, int32_t b, int32_t transpose_G,
                                     int32_t dtype, void* stream) {
@@ -138,13 +156,23 @@ int poetx_perm_validate(const int32_t* perm, int32_t d, int32_t* scratch, void* 
   return bad ? POETX_ERR_BAD_PERM : POETX_OK;
 }
 
+// The weight the dense product reads: W itself, or its dequantised copy made at `scratch`.
+static const void* resolve_weight(const poetx_linear_desc* desc, const void* W, void* scratch, hipStream_t st) {
+  if (!(desc->flags & POETX_FLAG_W_INT8)) return W;
+  StageTimer tm(POETX_STAGE_DENSE, st);   // timed with the product it feeds
+  weight_dequantize_q8_launch(W, desc->d_out, desc->d_in, desc->dtype, scratch, st);
+  return scratch;
+}
+
 size_t poetx_linear_workspace_bytes(const poetx_linear_desc* desc) {
   if (check_desc(desc) != POETX_OK) return 0;
   size_t es = esize(desc->dtype);
   size_t N = (size_t)desc->n_tokens;
   size_t fwd = align256((size_t)desc->d_in * N * es);   // A = R^T X
   if (desc->flags & POETX_FLAG_RECOMPUTE_B) fwd += align256((size_t)desc->d_out * N * es);  // B lives here too
-  size_t bwi = align256((size_t)desc->d_out * N * es);  // dB = P dZ
+  const size_t wdeq = (desc->flags & POETX_FLAG_W_INT8) ? align256((size_t)desc->d_out * desc->d_in * es) : 0;
+  fwd += wdeq;                                          // dequantised weight behind A (and B)
+  size_t bwi = align256((size_t)desc->d_out * N * es) + wdeq;  // dB = P dZ
   int dmax = desc->d_in > desc->d_out ? desc->d_in : desc->d_out;
   size_t bg_in = blockgrad_ws_bytes(desc->dtype, desc->d_in, desc->n_tokens, desc->block);
   size_t bg_out = blockgrad_ws_bytes(desc->dtype, desc->d_out, desc->n_tokens, desc->block);
@@ -165,7 +193,12 @@ int poetx_linear_fwd(const poetx_linear_desc* desc, const void* X, const void* W
   const int m = desc->d_in, n = desc->d_out, b = desc->block, dt = desc->dtype;
   const i64 N = desc->n_tokens;
   void* A = ws;
-  if (!saved_B) saved_B = (char*)ws + align256((size_t)m * N * esize(dt));  // memory-saving variant: scratch only
+  char* after = (char*)ws + align256((size_t)m * N * esize(dt));
+  if (!saved_B) {  // memory-saving variant: scratch only
+    saved_B = after;
+    after += align256((size_t)n * N * esize(dt));
+  }
+  W = resolve_weight(desc, W, after, st);
   apply_left_dispatch(dt, X, A, m, N, N, perm_R, blocks_R, b, 1, st);        // mm1: A = R^T X
   dense_dispatch(dt, 0, W, n, m, A, saved_B, N, st);                        // mm2: B = W A
   apply_left_dispatch(dt, saved_B, Z, n, N, N, perm_P, blocks_P, b, 1, st);  // mm3: Z = P^T B
@@ -181,6 +214,7 @@ int poetx_linear_recompute_b(const poetx_linear_desc* desc, const void* X, const
   hipStream_t st = (hipStream_t)stream;
   const int m = desc->d_in, n = desc->d_out, b = desc->block, dt = desc->dtype;
   const i64 N = desc->n_tokens;
+  W = resolve_weight(desc, W, (char*)ws + align256((size_t)m * N * esize(dt)), st);
   apply_left_dispatch(dt, X, ws, m, N, N, perm_R, blocks_R, b, 1, st);  // A = R^T X
   dense_dispatch(dt, 0, W, n, m, ws, B_out, N, st);                    // B = W A
   return launch_status();
@@ -197,6 +231,7 @@ int poetx_linear_bwd_input(const poetx_linear_desc* desc, const void* dZ, const 
   const int m = desc->d_in, n = desc->d_out, b = desc->block, dt = desc->dtype;
   const i64 N = desc->n_tokens;
   void* dB = ws;
+  W = resolve_weight(desc, W, (char*)ws + align256((size_t)n * N * esize(dt)), st);
   apply_left_dispatch(dt, dZ, dB, n, N, N, perm_P, blocks_P, b, 0, st);  // dB = P dZ
   dense_dispatch(dt, 1, W, n, m, dB, dA, N, st);                        // dA = W^T dB
   apply_left_dispatch(dt, dA, dX, m, N, N, perm_R, blocks_R, b, 0, st);  // dX = R dA

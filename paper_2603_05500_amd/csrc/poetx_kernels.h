@@ -38,6 +38,11 @@ void fma_cnp_bwd(const float* theta, const float* dG, int d, int b, int k, float
 // dtheta[j][idx(i,c)] (+)= M[j][i][c] - M[j][c][i] (Sec. 3.4: gradient on the packed parameters).
 void skew_project_launch(const float* M, int b, int d, float* dtheta, int accumulate, hipStream_t st);
 
+// ---- INT8 base weight (weight_q8.hip): codes [n][m] then, 256-byte aligned, float scale[n]
+size_t weight_q8_scale_offset(int n, int m);
+void weight_quantize_q8_launch(int dtype, const void* W, int n, int m, void* Wq, hipStream_t st);
+void weight_dequantize_q8_launch(const void* Wq, int n, int m, int dtype, void* W_out, hipStream_t st);
+
 void perm_validate_launch(const int32_t* perm, int d, int32_t* scratch, hipStream_t st);
 
 // ---- matrix-core path for bf16 (mfma_*.hip) -------------------------------------------

@@ -305,3 +305,78 @@ def test_mem_variant_matches_fast(lib, m, n, N, b, k, dtype):
     with pytest.raises(lib.PoetxError):
         lib.poetx_linear_fwd(dev["desc"], dev["X"], dev["W"], dev["pi_R"], dev["pi_P"], dev["blk_R"], dev["blk_P"],
                              Z, None, dev["ws"])
+
+
+# ------------------------------------------------------------------ quantised base weight (POET-XQ)
+def q8_views(buf, n, m):
+    """(codes int8 n x m, scales float32 n) of a quantised weight buffer brought to the host."""
+    raw = buf.cpu().numpy()
+    off = (n * m + 255) // 256 * 256
+    return raw[: n * m].view(np.int8).reshape(n, m), raw[off: off + 4 * n].view(np.float32)
+
+
+@pytest.mark.parametrize("n,m", [(37, 129), (256, 256), (512, 1376)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_weight_q8_codes_bit_exact(lib, n, m, dtype):
+    rng = RNG(8100 + n + m)
+    W = (round_f32 if dtype == "f32" else round_bf16)(rng.standard_normal((n, m)) * 0.02)
+    W[3] = 0.0                                           # an all-zero row: scale 1, codes 0
+    Wd = to_dev(W, tdtype(dtype))
+    buf = torch.zeros(lib.poetx_weight_q8_bytes(n, m), dtype=torch.uint8, device="cuda")
+    lib.poetx_weight_quantize_q8(Wd, buf)
+    out = torch.empty_like(Wd)
+    lib.poetx_weight_dequantize_q8(buf, out)
+    torch.cuda.synchronize()
+    q, s = q8_views(buf, n, m)
+    q_ref, s_ref = orc.weight_quantize_q8(W)
+    assert np.array_equal(s, s_ref)                      # fp32 scale, bit for bit
+    assert np.array_equal(q, q_ref)                      # integer codes, bit for bit
+    # the device forms scale * code in fp32 (exactly rounded) and rounds once more to the storage type
+    prod32 = s_ref[:, None] * q_ref.astype(np.float32)
+    expect = prod32.astype(np.float64) if dtype == "f32" else round_bf16(prod32.astype(np.float64))
+    assert np.array_equal(to_np(out), expect)
+    assert rel_err(to_np(out), orc.weight_dequantize_q8(q_ref, s_ref)) <= (1e-6 if dtype == "f32" else 2 ** -8)
+
+
+@pytest.mark.parametrize("m,n,N,b,k,dtype", [(256, 512, 256, 256, 4, "bf16"), (1376, 512, 384, 64, 4, "bf16"),
+                                             (96, 160, 128, 32, 3, "f32")])
+def test_xq_layer(lib, m, n, N, b, k, dtype):
+    """Memory-saving variant on an INT8 base weight: every product must be the oracle's on the
+    dequantised weight scale_i * q[i][k] (the oracle quantises with its own routine)."""
+    data = synth_layer(9700 + m + n, m, n, N, b, k, dtype)
+    q_ref, s_ref = orc.weight_quantize_q8(data["W"])
+    ref = orc.linear_fwd_bwd_from_theta(data["X"], data["dZ"], orc.weight_dequantize_q8(q_ref, s_ref), data["pi_R"],
+                                        data["pi_P"], data["theta_R"], data["theta_P"], b, k)
+    dt = tdtype(dtype)
+    code = lib.F32 if dtype == "f32" else lib.BF16
+    X, dZ, W = to_dev(data["X"], dt), to_dev(data["dZ"], dt), to_dev(data["W"], dt)
+    Wq = torch.zeros(lib.poetx_weight_q8_bytes(n, m), dtype=torch.uint8, device="cuda")
+    lib.poetx_weight_quantize_q8(W, Wq)
+    del W                                                # only the 8-bit weight is kept
+    pi_R, pi_P = torch.from_numpy(data["pi_R"]).cuda(), torch.from_numpy(data["pi_P"]).cuda()
+    th_R, th_P = to_dev(data["theta_R"], torch.float32), to_dev(data["theta_P"], torch.float32)
+    blk_R, G_R = build_blocks(data["theta_R"], m, b, k, dtype)
+    blk_P, G_P = build_blocks(data["theta_P"], n, b, k, dtype)
+    bad = lib.make_desc(m, n, b, k, N, code, flags=lib.FLAG_W_INT8)   # only valid in the variant that keeps no activation
+    assert lib.poetx_linear_workspace_bytes(bad) == 0
+    with pytest.raises(lib.PoetxError):
+        lib.poetx_linear_fwd(bad, X, Wq, pi_R, pi_P, blk_R, blk_P, torch.empty((n, N), dtype=dt, device="cuda"),
+                             torch.empty((n, N), dtype=dt, device="cuda"), ws_tensor(1 << 24))
+    desc = lib.make_desc(m, n, b, k, N, code, flags=lib.FLAG_RECOMPUTE_B | lib.FLAG_W_INT8)
+    plain = lib.make_desc(m, n, b, k, N, code, flags=lib.FLAG_RECOMPUTE_B)
+    es = 4 if dtype == "f32" else 2
+    assert lib.poetx_linear_workspace_bytes(desc) >= lib.poetx_linear_workspace_bytes(plain)
+    assert lib.poetx_linear_workspace_bytes(desc) >= (m + n) * N * es + n * m * es
+    ws = ws_tensor(lib.poetx_linear_workspace_bytes(desc))
+    Z = torch.empty((n, N), dtype=dt, device="cuda")
+    B = torch.empty((n, N), dtype=dt, device="cuda")
+    dX, dA = torch.empty((m, N), dtype=dt, device="cuda"), torch.empty((m, N), dtype=dt, device="cuda")
+    dR, dP = torch.full_like(th_R, float("nan")), torch.full_like(th_P, float("nan"))
+    lib.poetx_linear_fwd(desc, X, Wq, pi_R, pi_P, blk_R, blk_P, Z, None, ws)
+    lib.poetx_linear_bwd_input(desc, dZ, Wq, pi_R, pi_P, blk_R, blk_P, dX, dA, ws)
+    lib.poetx_linear_recompute_b(desc, X, Wq, pi_R, blk_R, B, ws)
+    lib.poetx_linear_bwd_skew(desc, X, dZ, B, dA, pi_R, pi_P, th_R, th_P, dR, dP, False, ws)
+    torch.cuda.synchronize()
+    res = {"G_R": G_R, "G_P": G_P, "Z": to_np(Z), "B": to_np(B), "dX": to_np(dX), "dtheta_R": to_np(dR),
+           "dtheta_P": to_np(dP)}
+    check_layer(res, ref, data["pi_P"], dtype)
