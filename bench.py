@@ -149,7 +149,7 @@ def micro(args, torch, px):
     g = torch.Generator(device="cuda")
     g.manual_seed(20260305)
     it = max(args.steps, 5)
-    out = {"apply_vs_hidden": [], "apply_vs_tokens": [], "cnp_build_k3": []}
+    out = {"apply_vs_hidden": [], "apply_vs_tokens": [], "cnp_build_k3": [], "merge": []}
     b = 256
 
     def apply_case(d, N):
@@ -164,6 +164,18 @@ def micro(args, torch, px):
         out["apply_vs_hidden"].append(apply_case(d, 8192))
     for N in (2048, 4096, 8192, 16384):      # block-diagonal table: sequence length sweep
         out["apply_vs_tokens"].append(apply_case(4096, N))
+    for n, m in ((4096, 4096), (14336, 4096), (4096, 14336)):   # merge W <- P^T W R^T on the stored weight (every 400 steps)
+        W = (torch.randn((n, m), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+        T1, T2 = torch.empty_like(W), torch.empty_like(W)
+        EP = (torch.randn((n // b, 2, b, b), generator=g, device="cuda") * 0.01).to(torch.bfloat16)
+        ER = (torch.randn((m // b, 2, b, b), generator=g, device="cuda") * 0.01).to(torch.bfloat16)
+        pP = torch.randperm(n, generator=g, device="cuda").to(torch.int32)
+        pR = torch.randperm(m, generator=g, device="cuda").to(torch.int32)
+
+        def merge():
+            px.poetx_perm_blockdiag_apply_left(W, T1, pP, EP, b, True)
+            px.poetx_perm_blockdiag_apply_right(T1, T2, pR, ER, b, True)
+        out["merge"].append({"out": n, "in": m, "ms": time_call(torch, merge, it)})
     for bb in (256, 512):                    # Cayley-Neumann table: number of blocks sweep, k = 3
         for nb in (64, 128, 192, 256, 320):
             d = nb * bb
