@@ -67,7 +67,8 @@ void mfma_blockgrad(const void* U, const void* V, int d, i64 N, const int32_t* p
   g.rows_per_batch = b;
   const i64 total = (i64)nb * b * b;
   float* part = splits > 1 ? (float*)ws : dG;
-  mm::launch<GBM, GBN, 2, 4, true, true, true>(g, EpiPartial{part, b, total}, nb, splits, st);
+  // a split contracts as few as 8 stages: no redundant tail loads
+  mm::launch<GBM, GBN, 2, 4, true, true, true, 4, true>(g, EpiPartial{part, b, total}, nb, splits, st);
   if (splits > 1)
     hipLaunchKernelGGL(reduce_partials_kernel, dim3(ceil_div(total / 4, 256)), dim3(256), 0, st, (const float4*)part,
                        (float4*)dG, total / 4, splits);

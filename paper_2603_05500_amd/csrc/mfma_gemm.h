@@ -139,14 +139,15 @@ __device__ inline void wait_tiles_and_barrier(int tiles) {
 // grid = (tiles_m * tiles_n, batches, splits).  With splits > 1 split z contracts k tiles
 // [z * ktiles, (z+1) * ktiles) of source 0.  Source::ktiles counts 64-deep tiles.
 //
-// NS = 4 keeps the loop free of branches: loads past the last tile re-fetch it, so one fixed
-// vmcnt bound serves every iteration.  Deeper rings (short contractions, where the latency of
-// the first tiles is the whole cost) stop issuing after the last tile and shrink the bound.
-template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, bool GATHER, int NS, class Epi>
+// EXACT_TAIL = false keeps the loop free of branches: loads past the last tile re-fetch it, so
+// one fixed vmcnt bound serves every iteration (NS - 1 redundant tile loads per workgroup:
+// nothing next to a long contraction).  With EXACT_TAIL the kernel stops issuing after the last
+// tile and shrinks the bound instead -- for short contractions, where redundant loads and the
+// latency of the first tiles are a visible share of the work.
+template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, bool GATHER, int NS, bool EXACT_TAIL, class Epi>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(Args g, Epi epi) {
   using C = Cfg<BM, BN, WGM, WGN, NS>;
   constexpr int NSTAGE = NS;
-  constexpr bool EXACT_TAIL = NS > 4;
   constexpr int TM = BM / WGM / 32, TN = BN / WGN / 32;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
 
@@ -357,10 +358,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(Args g, Epi e
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, bool GATHER, int NS = 4, class Epi>
+template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, bool GATHER, int NS = 4, bool EXACT_TAIL = (NS > 4),
+          class Epi>
 void launch(const Args& g, Epi epi, int batches, int splits, hipStream_t st) {
   using C = Cfg<BM, BN, WGM, WGN, NS>;
-  auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, A_KMAJOR, B_KMAJOR, GATHER, NS, Epi>;
+  auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, A_KMAJOR, B_KMAJOR, GATHER, NS, EXACT_TAIL, Epi>;
   static bool configured = false;
   if (!configured) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
