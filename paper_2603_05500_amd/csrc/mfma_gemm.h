@@ -6,7 +6,7 @@
 // Operand tiles go from global memory straight into LDS (global_load_lds, 16
 // bytes per lane, no staging registers) through a ring of NS stages of BK = 32
 // (4 for the long contractions, deeper for the short ones of the series kernels),
-// so NS - 2 tiles are in flight while one is multiplied and the only per-tile
+// so up to NS - 1 tiles are in flight while one is multiplied and the only per-tile
 // synchronisation is one barrier.  A tile is stored unpadded; bank conflicts are
 // avoided by an XOR swizzle of the 16-byte chunks, which costs nothing because
 // every lane may fetch any global chunk.
@@ -92,7 +92,7 @@ struct Args {
   int rows_per_batch;
 };
 
-// NS = ring depth (stages); NS - 2 tiles are in flight while one is multiplied.
+// NS = ring depth (stages); up to NS - 1 tiles are in flight while one is multiplied.
 template <int BM, int BN, int WGM, int WGN, int NS>
 struct Cfg {
   static constexpr int NWAVE = WGM * WGN;
@@ -121,15 +121,22 @@ __device__ inline void wait_vmcnt_and_barrier() {
   static_assert(N >= 0 && N < 64, "vmcnt range");
   asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
+// The same, and this wave's LDS reads have returned too (so that the stage they came from may
+// be overwritten by whoever passes the barrier).
+template <int N>
+__device__ inline void wait_all_reads_and_barrier() {
+  static_assert(N >= 0 && N < 64, "vmcnt range");
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
 
 // The same with a run-time (wave uniform) bound: at most min(tiles, MAXT) tiles of LPT loads
 // each may stay outstanding.  The count must be an immediate, hence the chain of cases.
 template <int LPT, int MAXT>
 __device__ inline void wait_tiles_and_barrier(int tiles) {
   if constexpr (MAXT <= 0) {
-    wait_vmcnt_and_barrier<0>();
+    wait_all_reads_and_barrier<0>();
   } else {
-    if (tiles >= MAXT) wait_vmcnt_and_barrier<MAXT * LPT>();
+    if (tiles >= MAXT) wait_all_reads_and_barrier<MAXT * LPT>();
     else wait_tiles_and_barrier<LPT, MAXT - 1>(tiles);
   }
 }
@@ -305,14 +312,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(Args g, Epi e
     }
   };
 
-  // Ring schedule.  Tiles kt+1 .. kt+NSTAGE-1 are in flight or landed while tile kt is
-  // multiplied.  At the top of iteration kt the wave waits for tile kt+1 (one tile ahead,
-  // so that its first fragments can be prefetched under the last MFMAs of tile kt), meets
-  // the other waves, and refills the stage that tile kt-1 has just vacated.
+  // Ring schedule.  All NS stages are in use: while tile kt is multiplied, tiles kt+1 ..
+  // kt+NS-1 are in flight or landed.  The one barrier per tile sits in the middle of the
+  // iteration: by then every wave holds all of tile kt in registers (its k step 0 fragments
+  // were prefetched during tile kt-1, its k step 1 fragments are waited for here), so the
+  // stage of tile kt is refilled at once with tile kt+NS, and tile kt+1 -- whose arrival the
+  // same wait checks -- can be prefetched under the second half of the MFMAs.
   constexpr int LPT = C::IPW_A + C::IPW_B;  // direct-to-LDS loads per tile per wave
-  // NS = 4: loads past the last tile re-fetch the last tile into a free stage, which keeps
+  static_assert(NSTAGE * LPT < 64, "vmcnt range");
+  // !EXACT_TAIL: loads past the last tile re-fetch the last tile into a free stage, which keeps
   // the number of outstanding loads constant (no branches, one fixed vmcnt bound).
-  static_assert((NSTAGE - 1) * LPT < 64, "vmcnt range");
   auto issue_clamped = [&](int t) {
     if (EXACT_TAIL) {
       if (t < KT) issue_at(t, t % NSTAGE);
@@ -320,23 +329,22 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(Args g, Epi e
       issue_at(t < KT ? t : KT - 1, t % NSTAGE);
     }
   };
-  // tiles issued before tile t's turn at the top of the loop, and so the number of tiles
-  // younger than tile `need` that may still be in flight there
-  auto younger_than = [&](int issued_upto, int need) { return (issued_upto < KT ? issued_upto : KT) - 1 - need; };
+  // with `issued` tiles issued so far, the number of tiles younger than tile `need`
+  auto younger_than = [&](int issued, int need) { return (issued < KT ? issued : KT) - 1 - need; };
 #pragma unroll
-  for (int t = 0; t < NSTAGE - 1; ++t) issue_clamped(t);
-  if (EXACT_TAIL) wait_tiles_and_barrier<LPT, NSTAGE - 2>(younger_than(NSTAGE - 1, 0));
-  else wait_vmcnt_and_barrier<(NSTAGE - 2) * LPT>();
+  for (int t = 0; t < NSTAGE; ++t) issue_clamped(t);
+  if (EXACT_TAIL) wait_tiles_and_barrier<LPT, NSTAGE - 1>(younger_than(NSTAGE, 0));
+  else wait_vmcnt_and_barrier<(NSTAGE - 1) * LPT>();
   Frags F, G;
   load_frags(F, 0, 0);
   for (int kt = 0; kt < KT; ++kt) {
-    // tile kt+1 has landed, for every wave
-    if (EXACT_TAIL) wait_tiles_and_barrier<LPT, NSTAGE - 3>(younger_than(kt + NSTAGE - 1, kt + 1));
-    else wait_vmcnt_and_barrier<(NSTAGE - 3) * LPT>();
-    issue_clamped(kt + NSTAGE - 1);                 // into the stage tile kt-1 vacated
     load_frags(G, kt, 1);
     mfma_all(F);
     interleave_hint();
+    // tile kt+1 has landed and tile kt is in registers, for every wave
+    if (EXACT_TAIL) wait_tiles_and_barrier<LPT, NSTAGE - 2>(younger_than(kt + NSTAGE, kt + 1));
+    else wait_all_reads_and_barrier<(NSTAGE - 2) * LPT>();
+    issue_clamped(kt + NSTAGE);                     // into the stage of tile kt
     load_frags(F, kt + 1, 0);                       // stale but harmless after the last tile
     mfma_all(G);
     interleave_hint();
