@@ -70,3 +70,26 @@ def test_host_argument_checks(clib):
     assert clib.poetx_linear_bwd_input(ctypes.byref(d2), *args, 1 << 30, None) == 1
     d3 = px.make_desc(256, 16, 32, 4, 512, px.F32)
     assert clib.poetx_linear_bwd_skew(ctypes.byref(d3), *([fake] * 10), 0, fake, 1 << 30, None) == 2
+
+
+def test_flag_and_quantised_weight_checks(clib):
+    fake = ctypes.c_void_p(0x1000)
+    plain = px.make_desc(256, 512, 32, 4, 512, px.BF16)
+    mem = px.make_desc(256, 512, 32, 4, 512, px.BF16, flags=px.FLAG_RECOMPUTE_B)
+    xq = px.make_desc(256, 512, 32, 4, 512, px.BF16, flags=px.FLAG_RECOMPUTE_B | px.FLAG_W_INT8)
+    only_q = px.make_desc(256, 512, 32, 4, 512, px.BF16, flags=px.FLAG_W_INT8)
+    unknown = px.make_desc(256, 512, 32, 4, 512, px.BF16, flags=8)
+    w_plain, w_mem, w_xq = (px.poetx_linear_workspace_bytes(d) for d in (plain, mem, xq))
+    assert w_mem >= (256 + 512) * 512 * 2 and w_mem >= w_plain
+    assert w_xq >= w_mem and w_xq >= (256 + 512) * 512 * 2 + 512 * 256 * 2     # + one dequantised weight
+    assert px.poetx_linear_workspace_bytes(only_q) == 0                          # INT8 weight needs the no-activation variant
+    assert px.poetx_linear_workspace_bytes(unknown) == 0
+    assert clib.poetx_linear_fwd(ctypes.byref(only_q), *([fake] * 9), 1 << 30, None) == 1
+    # saved_B may be absent only in the memory-saving variant
+    args = [fake] * 7 + [None, fake]
+    assert clib.poetx_linear_fwd(ctypes.byref(plain), *args, 1 << 30, None) == 1
+    assert px.poetx_weight_q8_bytes(512, 256) >= 512 * 256 + 4 * 512
+    assert px.poetx_weight_q8_bytes(0, 256) == 0
+    assert clib.poetx_weight_quantize_q8(None, px.BF16, 8, 8, fake, None) == 1
+    assert clib.poetx_weight_quantize_q8(fake, 5, 8, 8, fake, None) == 1
+    assert clib.poetx_weight_dequantize_q8(fake, 8, 0, px.BF16, fake, None) == 1
