@@ -72,18 +72,26 @@ def make_inputs(cfg, torch):
         d["X"] = torch.randn((m, N), generator=g, device="cuda", dtype=torch.float32).to(dt)
         d["dZ"] = torch.randn((n, N), generator=g, device="cuda", dtype=torch.float32).to(dt)
         d["W"] = (torch.randn((n, m), generator=g, device="cuda", dtype=torch.float32) * cfg.sigma_w).to(dt)
+        # The packed parameters (and the blocks built from them) of the two sides of a projection live
+        # in one buffer, R side first, so that one poetx_cnp_build call covers both sides when b
+        # divides both dimensions (the series of a block does not depend on which side it belongs to).
+        nbs = {"R": -(-m // b), "P": -(-n // b)}
+        d["theta_all"] = torch.randn((nbs["R"] + nbs["P"], b * (b - 1) // 2), generator=g, device="cuda",
+                                     dtype=torch.float32) * cfg.sigma_theta
+        bshape = (nbs["R"] + nbs["P"], 2, b, b) if cfg.dtype == "bf16" else (nbs["R"] + nbs["P"], b, b)
+        d["blk_all"] = torch.empty(bshape, device="cuda", dtype=dt)   # bf16: (G - I, its transpose)
+        d["one_build"] = m % b == 0 and n % b == 0
         for side, dim in (("R", m), ("P", n)):
-            nb = -(-dim // b)
-            d["theta_" + side] = torch.randn((nb, b * (b - 1) // 2), generator=g, device="cuda",
-                                             dtype=torch.float32) * cfg.sigma_theta
+            nb = nbs[side]
+            lo = 0 if side == "R" else nbs["R"]
+            d["theta_" + side] = d["theta_all"][lo:lo + nb]
             # fresh permutations per step (Sec. 3, merge-and-resample): a pool of index vectors made
             # before the timed region, walked round robin; permutations are inputs of every call, so a new
             # one costs the path nothing
             npool = 4 if cfg.fresh_perms else 1
             d["pool_" + side] = [torch.randperm(dim, generator=g, device="cuda").to(torch.int32) for _ in range(npool)]
             d["pi_" + side] = d["pool_" + side][0]
-            shape = (nb, 2, b, b) if cfg.dtype == "bf16" else (nb, b, b)  # bf16: (G - I, its transpose)
-            d["blk_" + side] = torch.empty(shape, device="cuda", dtype=dt)
+            d["blk_" + side] = d["blk_all"][lo:lo + nb]
             d["dtheta_" + side] = torch.empty_like(d["theta_" + side])
         projs.append(d)
     return projs
@@ -230,7 +238,7 @@ def main():
             torch.cuda.synchronize()
             p["W"] = wq
         ws_bytes = max(ws_bytes, px.poetx_linear_workspace_bytes(p["desc"]))
-        cnp_bytes = max(cnp_bytes, px.poetx_cnp_workspace_bytes(max(p["m"], p["n"]), b))
+        cnp_bytes = max(cnp_bytes, px.poetx_cnp_workspace_bytes(p["m"] + p["n"], b))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     cws = torch.empty(cnp_bytes, dtype=torch.uint8, device="cuda")
     prec = px.CNP_BF16 if code == px.BF16 else px.CNP_FP32
@@ -242,10 +250,14 @@ def main():
             m, n = p["m"], p["n"]
             p["pi_R"] = p["pool_R"][step_no[0] % len(p["pool_R"])]
             p["pi_P"] = p["pool_P"][step_no[0] % len(p["pool_P"])]
-            kw = {"E_bf16": p["blk_R"]} if code == px.BF16 else {"G_f32": p["blk_R"]}
-            px.poetx_cnp_build(p["theta_R"], m, b, k, prec, ws=cws, **kw)
-            kw = {"E_bf16": p["blk_P"]} if code == px.BF16 else {"G_f32": p["blk_P"]}
-            px.poetx_cnp_build(p["theta_P"], n, b, k, prec, ws=cws, **kw)
+            if p["one_build"]:
+                kw = {"E_bf16": p["blk_all"]} if code == px.BF16 else {"G_f32": p["blk_all"]}
+                px.poetx_cnp_build(p["theta_all"], m + n, b, k, prec, ws=cws, **kw)
+            else:
+                kw = {"E_bf16": p["blk_R"]} if code == px.BF16 else {"G_f32": p["blk_R"]}
+                px.poetx_cnp_build(p["theta_R"], m, b, k, prec, ws=cws, **kw)
+                kw = {"E_bf16": p["blk_P"]} if code == px.BF16 else {"G_f32": p["blk_P"]}
+                px.poetx_cnp_build(p["theta_P"], n, b, k, prec, ws=cws, **kw)
             px.poetx_linear_fwd(p["desc"], p["X"], p["W"], p["pi_R"], p["pi_P"], p["blk_R"], p["blk_P"],
                                 Z[:n], None if args.variant != "fast" else B[:n], ws)
             px.poetx_linear_bwd_input(p["desc"], p["dZ"], p["W"], p["pi_R"], p["pi_P"], p["blk_R"], p["blk_P"],

@@ -14,10 +14,10 @@
 namespace poetx {
 namespace {
 
-// Small output tiles: one side has only a few blocks, so 64 x 64 tiles are what fills the 256 CUs.
-// A contraction is only b deep, so the latency of the first tiles is most of a launch: an
-// 8-deep ring puts six 8 KB tiles in flight at once (64 KB of LDS, two workgroups per CU).
-constexpr int CBM = 64, CBN = 64, CBK = 64, CNS = 8;
+// Tiled products (block sides that do not fit on chip, i.e. b = 512): 128 x 128 tiles, 2 x 2 waves,
+// 64 KB of LDS so that two workgroups share a CU; a contraction is only b deep, so the loop
+// stops loading after the last tile instead of re-fetching it.
+constexpr int CBM = 128, CBN = 128, CBK = 64, CNS = 4;
 
 __device__ inline float skew_at(const float* th, int i, int c, int b) {
   if (i == c) return 0.f;
@@ -122,6 +122,11 @@ void set_src(mm::Source& s, const uint16_t* A, const uint16_t* B, int b) {
 
 }  // namespace
 
+void skew_materialize_launch(const float* theta, int b, i64 nb, float* Qf, uint16_t* Qb, uint16_t* Tb, hipStream_t st) {
+  const i64 total = nb * b * b;
+  hipLaunchKernelGGL(skew_materialize_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, theta, b, total, Qf, Qb, Tb);
+}
+
 bool mfma_cnp_supported(int d, int b) { return (b == 256 || b == 512) && d % b == 0; }
 
 // bytes of scratch per block element (nb*b*b elements): forward Qf(4) + Qb, H0, H1 (2 each);
@@ -149,7 +154,7 @@ void mfma_cnp_build(const float* theta, int d, int b, int k, float* G_f32, void*
     set_src(g.s[0], cur, Qb, b);
     uint16_t* nxt = H[step & 1];
     EpiHorner epi{Qf, 2.f, b, last ? nullptr : nxt, last ? G_f32 : nullptr, last ? (uint16_t*)E_bf16 : nullptr};
-    mm::launch<CBM, CBN, 2, 2, true, false, false, CNS>(g, epi, nb, 1, st);
+    mm::launch<CBM, CBN, 2, 2, true, false, false, CNS, true>(g, epi, nb, 1, st);
     cur = nxt;
   }
 }
@@ -160,19 +165,27 @@ void mfma_cnp_bwd(const float* theta, const float* dG, int d, int b, int k, floa
   const i64 total = (i64)nb * b * b;
   if (lds_cnp_supported(d, b)) {   // two launches, block resident in LDS; scratch = bf16(Q) + (k + 1) fp32 matrices
     uint16_t* Qb = (uint16_t*)ws;
-    hipLaunchKernelGGL(skew_materialize_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, theta, b, total,
-                       (float*)nullptr, Qb, (uint16_t*)nullptr);
-    lds_cnp_bwd(Qb, dG, d, k, dtheta, accumulate, ws + total, st);
+    skew_materialize_launch(theta, b, nb, nullptr, Qb, nullptr, st);
+    const float* dQ = lds_cnp_bwd_chain(Qb, dG, nb, k, ws + total, st);
+    skew_project_launch(dQ, b, d, dtheta, accumulate, st);
     return;
   }
   float* Qf = ws;
-  float* Bfinal = Qf + total;
-  uint16_t* Tb = (uint16_t*)(Bfinal + total);
-  uint16_t* Db = Tb + total;
-  uint16_t* A[2] = {Tb + 2 * total, Tb + 3 * total};
-  uint16_t* Bb[2] = {Tb + 4 * total, Tb + 5 * total};
-  hipLaunchKernelGGL(skew_materialize_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, theta, b, total, Qf,
-                     (uint16_t*)nullptr, Tb);
+  uint16_t* Tb = (uint16_t*)(Qf + total);
+  skew_materialize_launch(theta, b, nb, Qf, nullptr, Tb, st);
+  const float* dQ = mfma_cnp_bwd_chain(Qf, Tb, dG, nb, b, k, Qf + total + total / 2, st);
+  skew_project_launch(dQ, b, d, dtheta, accumulate, st);
+}
+
+// Tiled two-sided Horner backward for nb blocks (of any sides) given Q in fp32 and T = -Q in
+// bf16; ws: 3.5 floats per block element.  Returns dL/dQ (inside ws).
+const float* mfma_cnp_bwd_chain(const float* Qf, const uint16_t* Tb, const float* dG, int nb, int b, int k, float* ws,
+                                hipStream_t st) {
+  const i64 total = (i64)nb * b * b;
+  float* Bfinal = ws;
+  uint16_t* Db = (uint16_t*)(Bfinal + total);
+  uint16_t* A[2] = {Db + total, Db + 2 * total};
+  uint16_t* Bb[2] = {Db + 3 * total, Db + 4 * total};
   hipLaunchKernelGGL(to_bf16_kernel, dim3(ceil_div(total / 4, 256)), dim3(256), 0, st, (const float4*)dG, (uint2*)Db,
                      total / 4);
   const uint16_t* acur = Tb;  // A'_1 = T
@@ -190,7 +203,7 @@ void mfma_cnp_bwd(const float* theta, const float* dG, int d, int b, int k, floa
       set_src(g.alt[0], acur, Tb, b);
     }
     EpiBwdStep epi{dG, Qf, b, nb, last ? nullptr : Bb[ib], last ? Bfinal : nullptr, last ? nullptr : A[ia]};
-    mm::launch<CBM, CBN, 2, 2, true, false, false, CNS>(g, epi, last ? nb : 2 * nb, 1, st);
+    mm::launch<CBM, CBN, 2, 2, true, false, false, CNS, true>(g, epi, last ? nb : 2 * nb, 1, st);
     if (!last) {
       acur = A[ia];
       ia ^= 1;
@@ -198,7 +211,7 @@ void mfma_cnp_bwd(const float* theta, const float* dG, int d, int b, int k, floa
       ib ^= 1;
     }
   }
-  skew_project_launch(Bfinal, b, d, dtheta, accumulate, st);
+  return Bfinal;
 }
 
 }  // namespace poetx

@@ -326,18 +326,17 @@ void lds_cnp_build(const float* Qf, const uint16_t* Qb, int d, int k, float* G_f
   launch_chain<CHAIN_FWD>(a, st);
 }
 
-void lds_cnp_bwd(const uint16_t* Qb, const float* dG, int d, int k, float* dtheta, int accumulate, float* ws,
-                 hipStream_t st) {
+const float* lds_cnp_bwd_chain(const uint16_t* Qb, const float* dG, int nb, int k, float* ws, hipStream_t st) {
   ChainArgs a{};
   a.Qb = Qb;
   a.k = k;
-  a.nb = d / LB;
+  a.nb = nb;
   a.D = dG;
   a.M = ws;
-  a.dQ = ws + (size_t)k * a.nb * LB * LB;
+  a.dQ = ws + (size_t)k * nb * LB * LB;
   launch_chain<CHAIN_BWD1>(a, st);
   launch_chain<CHAIN_BWD2>(a, st);
-  skew_project_launch(a.dQ, LB, d, dtheta, accumulate, st);
+  return a.dQ;
 }
 
 }  // namespace poetx

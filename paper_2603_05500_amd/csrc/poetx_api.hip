@@ -40,6 +40,11 @@ size_t cnp_bwd_ws_floats(int d, int b, int k) {
   const size_t per_elem = 1 + (size_t)(k + 2 > 5 ? k + 2 : 5);
   return per_elem * ceil_div(d, b) * b * b;
 }
+// The same when both sides of a layer go through the series backward together.
+size_t cnp_bwd_ws_floats_both(int m, int n, int b, int k) {
+  const size_t per_elem = (size_t)(k + 3 > 6 ? k + 3 : 6);   // tiled kernels: dG, Q, -Q (half), 3.5 of chain
+  return per_elem * (ceil_div(m, b) + ceil_div(n, b)) * b * b;
+}
 
 void apply_left_dispatch(int dtype, const void* V, void* out, int d, i64 cols, i64 ld, const int32_t* perm,
                          const void* blocks, int b, int trans, hipStream_t st) {
@@ -176,7 +181,10 @@ size_t poetx_linear_workspace_bytes(const poetx_linear_desc* desc) {
   int dmax = desc->d_in > desc->d_out ? desc->d_in : desc->d_out;
   size_t bg_in = blockgrad_ws_bytes(desc->dtype, desc->d_in, desc->n_tokens, desc->block);
   size_t bg_out = blockgrad_ws_bytes(desc->dtype, desc->d_out, desc->n_tokens, desc->block);
-  size_t skew = align256(cnp_bwd_ws_floats(dmax, desc->block, desc->neumann_k) * sizeof(float)) + (bg_in > bg_out ? bg_in : bg_out);
+  size_t chain = cnp_bwd_ws_floats(dmax, desc->block, desc->neumann_k);
+  const size_t both = cnp_bwd_ws_floats_both(desc->d_in, desc->d_out, desc->block, desc->neumann_k);
+  if (both > chain) chain = both;
+  size_t skew = align256(chain * sizeof(float)) + (bg_in > bg_out ? bg_in : bg_out);
   size_t w = fwd > bwi ? fwd : bwi;
   return w > skew ? w : skew;
 }
@@ -251,9 +259,50 @@ int poetx_linear_bwd_skew(const poetx_linear_desc* desc, const void* X, const vo
   const int m = desc->d_in, n = desc->d_out, b = desc->block, dt = desc->dtype, k = desc->neumann_k;
   const i64 N = desc->n_tokens;
   const int dmax = m > n ? m : n;
+  size_t chain_floats = cnp_bwd_ws_floats(dmax, b, k);
+  if (cnp_bwd_ws_floats_both(m, n, b, k) > chain_floats) chain_floats = cnp_bwd_ws_floats_both(m, n, b, k);
+  void* bg_ws = (char*)ws + align256(chain_floats * sizeof(float));
+  if (desc->cnp_precision == POETX_CNP_BF16 && !g_force_fma.load() && use_mfma(dt) && mfma_cnp_supported(m, b) &&
+      mfma_cnp_supported(n, b) && mfma_blockgrad_supported(m, N, b) && mfma_blockgrad_supported(n, N, b)) {
+    // Both sides' blocks go through the series backward as one batch (P side first): the chains
+    // are latency bound and a side alone leaves most CUs empty.
+    const int nbP = n / b, nbR = m / b, nbt = nbP + nbR;
+    const size_t bb = (size_t)b * b;
+    float* dG = (float*)ws;                                   // [nbt][b][b]
+    if (!lds_cnp_supported(m, b)) {                            // tiled kernels (b = 512)
+      float* Qf = dG + nbt * bb;
+      uint16_t* Tb = (uint16_t*)(Qf + nbt * bb);
+      float* chain = Qf + nbt * bb + nbt * bb / 2;            // 3.5 floats per element follow: 6 in all
+      {
+        StageTimer tm(POETX_STAGE_BLOCKGRAD, st);
+        mfma_blockgrad(saved_B, dZ, n, N, perm_P, b, dG, bg_ws, st);
+        mfma_blockgrad(X, dA, m, N, perm_R, b, dG + nbP * bb, bg_ws, st);
+      }
+      StageTimer tm(POETX_STAGE_CNP_BWD, st);
+      skew_materialize_launch(theta_P, b, nbP, Qf, nullptr, Tb, st);
+      skew_materialize_launch(theta_R, b, nbR, Qf + nbP * bb, nullptr, Tb + nbP * bb, st);
+      const float* dQ = mfma_cnp_bwd_chain(Qf, Tb, dG, nbt, b, k, chain, st);
+      skew_project_launch(dQ, b, n, dtheta_P, accumulate != 0, st);
+      skew_project_launch(dQ + nbP * bb, b, m, dtheta_R, accumulate != 0, st);
+      return launch_status();
+    }
+    uint16_t* Qb = (uint16_t*)(dG + nbt * bb);                // [nbt][b][b] bf16 (one float slot per element)
+    float* chain = dG + 2 * nbt * bb;                         // (k + 1) * nbt * b * b floats
+    {
+      StageTimer tm(POETX_STAGE_BLOCKGRAD, st);
+      mfma_blockgrad(saved_B, dZ, n, N, perm_P, b, dG, bg_ws, st);            // dG_P = B' dZ'^T
+      mfma_blockgrad(X, dA, m, N, perm_R, b, dG + nbP * bb, bg_ws, st);       // dG_R = X' dA'^T
+    }
+    StageTimer tm(POETX_STAGE_CNP_BWD, st);
+    skew_materialize_launch(theta_P, b, nbP, nullptr, Qb, nullptr, st);
+    skew_materialize_launch(theta_R, b, nbR, nullptr, Qb + nbP * bb, nullptr, st);
+    const float* dQ = lds_cnp_bwd_chain(Qb, dG, nbt, k, chain, st);
+    skew_project_launch(dQ, b, n, dtheta_P, accumulate != 0, st);
+    skew_project_launch(dQ + nbP * bb, b, m, dtheta_R, accumulate != 0, st);
+    return launch_status();
+  }
   float* dG = (float*)ws;
   float* chain = dG + (size_t)ceil_div(dmax, b) * b * b;
-  void* bg_ws = (char*)ws + align256(cnp_bwd_ws_floats(dmax, b, k) * sizeof(float));
   for (int side = 0; side < 2; ++side) {
     const void* U = side == 0 ? saved_B : X;   // mm3 backward: dG_P = B' dZ'^T; mm1 backward: dG_R = X' dA'^T
     const void* V = side == 0 ? dZ : dA;

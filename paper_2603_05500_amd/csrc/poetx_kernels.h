@@ -65,7 +65,15 @@ void mfma_cnp_bwd(const float* theta, const float* dG, int d, int b, int k, floa
 // Qf / Qb: Q in fp32 / bf16, [nb][b][b].  The backward needs (k + 1) * nb*b*b floats of scratch.
 bool lds_cnp_supported(int d, int b);
 void lds_cnp_build(const float* Qf, const uint16_t* Qb, int d, int k, float* G_f32, void* E_bf16, hipStream_t st);
-void lds_cnp_bwd(const uint16_t* Qb, const float* dG, int d, int k, float* dtheta, int accumulate, float* ws,
-                 hipStream_t st);
+// dL/dG of nb blocks -> dL/dQ (returned pointer lies inside ws); the blocks may belong to
+// several sides, the chain does not care.
+const float* lds_cnp_bwd_chain(const uint16_t* Qb, const float* dG, int nb, int k, float* ws, hipStream_t st);
+// Q of nb blocks from packed parameters: Qf fp32 and/or Qb bf16, [nb][b][b] (either may be null).
+// Tb = bf16(-Q).
+void skew_materialize_launch(const float* theta, int b, i64 nb, float* Qf, uint16_t* Qb, uint16_t* Tb, hipStream_t st);
+// Series backward on the tiled kernels (b = 512) for nb blocks: Qf fp32, Tb = bf16(-Q); ws holds
+// 3.5 floats per block element; returns dL/dQ (inside ws).
+const float* mfma_cnp_bwd_chain(const float* Qf, const uint16_t* Tb, const float* dG, int nb, int b, int k, float* ws,
+                                hipStream_t st);
 
 }  // namespace poetx
