@@ -277,7 +277,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    px.poetx_profile_begin(1 << 16)
+    # Timed region: exactly `steps` steps, nothing else on the stream.
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -288,6 +288,17 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     ms = e0.elapsed_time(e1) / args.steps
+    # Second pass over the same steps with the library's stage events switched on: per-stage split and
+    # the dense kernel's launch durations.  Kept apart from the timed region because the ~260 event
+    # records per step cost a few per cent of it.
+    px.poetx_profile_begin(1 << 16)
+    e2, e3 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e2.record()
+    for _ in range(args.steps):
+        step()
+    e3.record()
+    torch.cuda.synchronize()
+    ms_split = e2.elapsed_time(e3) / args.steps
     stages = px.poetx_profile_end()
     assert all(torch.isfinite(p["dtheta_R"]).all() and torch.isfinite(p["dtheta_P"]).all() for p in projs)
 
@@ -313,6 +324,7 @@ def main():
         "mfma_peak_frac_layer": (dense_f + block_f + cnp_f) / (ms * 1e-3) / (PEAK_BF16_TFLOPS * 1e12),
         "algorithmic_tflop_per_step": (dense_f + block_f + cnp_f) / 1e12,
         "wall_ms_per_step": wall_ms / args.steps,
+        "ms_per_step_with_stage_events": ms_split,
         "stage_ms_per_step": {s: v[0] / args.steps for s, v in stages.items()},
         "stage_rates": {
             "dense_TFLOPs": dense_tflops,
