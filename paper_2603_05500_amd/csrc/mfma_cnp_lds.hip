@@ -49,9 +49,6 @@ struct ChainArgs {
   float* dQ;            // backward pass 2: dL/dQ [nb][LB][LB]
 };
 
-// slot of contraction index k inside a row of Q in LDS (bits 2 and 3 swapped)
-__device__ inline int kslot(int k) { return (k & ~12) | ((k & 8) >> 1) | ((k & 4) << 1); }
-
 // p + n with the sum hidden from the optimiser: walking a column row by row with this keeps
 // one live address instead of one precomputed 64-bit address per unrolled access.
 template <class T>
