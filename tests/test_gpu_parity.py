@@ -248,6 +248,18 @@ def test_on_chip_series_orders(lib, k):
     check_layer(res, ref, data["pi_P"], "bf16")
 
 
+@pytest.mark.parametrize("N", [64, 128, 192, 320, 384, 576])
+def test_kernel_family_boundaries(lib, N):
+    """Token counts around the tile sizes of the matrix-core kernels (128-token apply tiles, 256-token
+    dense tiles, 64-token reduction tiles): each stage falls back to the plain kernels on its own
+    when its tiling does not fit, so every mix of the two families must still match the oracle."""
+    m, n, b, k = 512, 256, 256, 2
+    data = synth_layer(7400 + N, m, n, N, b, k, "bf16", 0.005)
+    ref = orc.linear_fwd_bwd_from_theta(data["X"], data["dZ"], data["W"], data["pi_R"], data["pi_P"],
+                                        data["theta_R"], data["theta_P"], b, k)
+    check_layer(run_layer(data, "bf16"), ref, data["pi_P"], "bf16")
+
+
 # ------------------------------------------------------------------ merge step W <- R W P
 @pytest.mark.parametrize("m,n,b,dtype", [(256, 512, 256, "bf16"), (96, 160, 32, "f32"), (1376, 512, 64, "bf16")])
 def test_merge_step(lib, m, n, b, dtype):
