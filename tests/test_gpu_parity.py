@@ -392,3 +392,50 @@ def test_xq_layer(lib, m, n, N, b, k, dtype):
     res = {"G_R": G_R, "G_P": G_P, "Z": to_np(Z), "B": to_np(B), "dX": to_np(dX), "dtheta_R": to_np(dR),
            "dtheta_P": to_np(dP)}
     check_layer(res, ref, data["pi_P"], dtype)
+
+
+# ------------------------------------------------------------------ stream capture
+def test_step_can_be_captured_in_a_graph(lib):
+    """The library enqueues kernels only (no allocation, no memset, no synchronisation on the hot
+    path), so a whole layer step can be stream-captured.  Every replay, with eager work and
+    synchronisations in between, must reproduce the eager result bit for bit."""
+    m, n, N, b, k = 256, 512, 256, 256, 3
+    data = synth_layer(9900, m, n, N, b, k, "bf16", 0.005)
+    eager = run_layer(data, "bf16")            # also warms every kernel up (function attributes are set on first use)
+    dev = eager["dev"]
+    desc, ws = dev["desc"], dev["ws"]
+    nbR = m // b
+    theta_all = torch.cat([dev["th_R"], dev["th_P"]]).contiguous()
+    blk_all = torch.empty((nbR + n // b, 2, b, b), dtype=torch.bfloat16, device="cuda")
+    cws = ws_tensor(lib.poetx_cnp_workspace_bytes(m + n, b))
+    Z, B = torch.empty_like(dev["Z"]), torch.empty_like(dev["B"])
+    dX, dA = torch.empty_like(dev["dX"]), torch.empty_like(dev["dA"])
+    dR, dP = torch.empty_like(dev["th_R"]), torch.empty_like(dev["th_P"])
+
+    def step():
+        lib.poetx_cnp_build(theta_all, m + n, b, k, lib.CNP_BF16, E_bf16=blk_all, ws=cws)
+        bR, bP = blk_all[:nbR], blk_all[nbR:]
+        lib.poetx_linear_fwd(desc, dev["X"], dev["W"], dev["pi_R"], dev["pi_P"], bR, bP, Z, B, ws)
+        lib.poetx_linear_bwd_input(desc, dev["dZ"], dev["W"], dev["pi_R"], dev["pi_P"], bR, bP, dX, dA, ws)
+        lib.poetx_linear_bwd_skew(desc, dev["X"], dev["dZ"], B, dA, dev["pi_R"], dev["pi_P"], dev["th_R"], dev["th_P"],
+                                  dR, dP, False, ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (Z, B, dX, dR, dP)]
+    assert torch.equal(Z, dev["Z"]) and torch.equal(dX, dev["dX"])     # one batched block build == two separate ones
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        for t in (Z, B, dX, dR, dP):
+            t.fill_(float("nan"))                                    # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref_t in zip((Z, B, dX, dR, dP), want):
+            assert torch.equal(got, ref_t), f"replay {rep} differs from the eager step"
