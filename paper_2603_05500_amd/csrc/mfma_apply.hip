@@ -228,14 +228,7 @@ __global__ __launch_bounds__(512) void apply_left_stream_kernel(const uint16_t* 
     if (t > 0) flush(t - 1);
     if (t + 1 < tiles_per_wg) issue(t + 1);
     const char* stage = ring + (t & 1) * STAGE_BYTES;
-    floatx16 acc[TN];
-#pragma unroll
-    for (int c = 0; c < TN; ++c)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      bf16x8 fb[TN];
+    auto load_tok = [&](bf16x8* fb, int ks) {
 #pragma unroll
       for (int c = 0; c < TN; ++c) {
         const char* p = stage + fragB[c] + ks * 16 * (BN * 2);
@@ -244,13 +237,29 @@ __global__ __launch_bounds__(512) void apply_left_stream_kernel(const uint16_t* 
         short8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         fb[c] = __builtin_bit_cast(bf16x8, v);
       }
+    };
+    floatx16 acc[TN];
 #pragma unroll
-      for (int c = 0; c < TN; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c], fa[ks], acc[c], 0, 0, 0);
-      if ((ks >> 1) == own_kpair) {  // wave uniform: these 16 l values lie in the wave's own rows
+    for (int c = 0; c < TN; ++c)
 #pragma unroll
-        for (int c = 0; c < TN; ++c)
-          acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c], fi[ks & 1], acc[c], 0, 0, 0);
-      }
+      for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
+    // identity part first (the two k steps that cover the wave's own rows: a wave-uniform LDS
+    // address, no branch in the main loop), then the block operand with the token fragments of
+    // the next k step always in flight under the MFMAs of the current one
+    bf16x8 fo[2][TN], fb[2][TN];
+    load_tok(fo[0], 2 * own_kpair);
+    load_tok(fo[1], 2 * own_kpair + 1);
+    load_tok(fb[0], 0);
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int c = 0; c < TN; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo[u][c], fi[u], acc[c], 0, 0, 0);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + 1 < KS) load_tok(fb[(ks + 1) & 1], ks + 1);
+#pragma unroll
+      for (int c = 0; c < TN; ++c)
+        acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks & 1][c], fa[ks], acc[c], 0, 0, 0);
     }
 #pragma unroll
     for (int c = 0; c < TN; ++c)
