@@ -349,3 +349,34 @@ def test_q8_half_steps_round_to_even():
     q, sc = orc.weight_quantize_q8(row[None, :])
     assert sc[0] == s
     assert q[0].tolist() == [127, 0, 2, 2, 0, -2, -2, 126]
+
+
+# ------------------------------------------------------------------ the two-pass form of the series backward
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5, 6])
+def test_series_backward_two_pass_regrouping(k):
+    """The on-chip backward kernels evaluate dL/dQ as  Y_0 = D, Y_m = W_m^T - Q Y_{m-1}, dL/dQ = Y_k  with
+    V_m = Q^m D^T and W_m = 2 (V_0 + .. + V_m) - V_m  (2k products, all left multiplications by Q).
+    Written out here in fp64 it must equal the oracle's double sum, which is pinned separately
+    against the paper's k = 3 display and against finite differences."""
+    rng = np.random.Generator(np.random.PCG64(600 + k))
+    b = 12
+    Q = orc.skew_from_packed(rng.standard_normal((1, b * (b - 1) // 2)) * 0.2, b)[0]
+    D = rng.standard_normal((b, b))
+    V = [D.T.copy()]
+    for _ in range(k):
+        V.append(Q @ V[-1])
+    S = np.zeros((b, b))
+    W = []
+    for m in range(k + 1):
+        S = S + V[m]
+        W.append(2.0 * S - V[m])
+    Y = D.copy()
+    for m in range(1, k + 1):
+        Y = W[m].T - Q @ Y
+    ref = orc.cnp_bwd(Q, D, k)
+    assert np.max(np.abs(Y - ref)) <= 1e-12 * max(1.0, np.max(np.abs(ref)))
+    # and the forward chain of the same kernels: H_1 = Q, H_{s+1} = 2Q + Q H_s, G = I + H_{k+1}
+    H = Q.copy()
+    for _ in range(k):
+        H = 2.0 * Q + Q @ H
+    assert np.max(np.abs(np.eye(b) + H - orc.cnp(Q, k))) <= 1e-13
