@@ -439,3 +439,38 @@ def test_step_can_be_captured_in_a_graph(lib):
         torch.cuda.synchronize()
         for got, ref_t in zip((Z, B, dX, dR, dP), want):
             assert torch.equal(got, ref_t), f"replay {rep} differs from the eager step"
+
+
+# ------------------------------------------------------------------ optional outputs / accumulation on the on-chip path
+def test_on_chip_build_optional_outputs(lib):
+    """b = 256, matrix-core series: G only, E only and both must give the same values."""
+    d, b, k = 512, 256, 4
+    theta = draw_theta(RNG(4321), d, b, 0.005)
+    th = to_dev(theta, torch.float32)
+    ws = ws_tensor(lib.poetx_cnp_workspace_bytes(d, b))
+    G1 = torch.empty((2, b, b), dtype=torch.float32, device="cuda")
+    G2 = torch.empty_like(G1)
+    E1 = torch.empty((2, 2, b, b), dtype=torch.bfloat16, device="cuda")
+    E2 = torch.empty_like(E1)
+    lib.poetx_cnp_build(th, d, b, k, lib.CNP_BF16, G1, E1, ws)
+    lib.poetx_cnp_build(th, d, b, k, lib.CNP_BF16, G2, None, ws)
+    lib.poetx_cnp_build(th, d, b, k, lib.CNP_BF16, None, E2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(G1, G2) and torch.equal(E1, E2)
+    ref = orc.cnp(orc.skew_from_packed(theta, b, d), k)
+    assert rel_err(to_np(G1) - np.eye(b), ref - np.eye(b)) <= 2e-2
+
+
+def test_bwd_skew_accumulates_on_the_batched_path(lib):
+    """accumulate != 0 adds to dtheta (both sides go through one batched series backward at b = 256)."""
+    m, n, N, b, k = 512, 256, 256, 256, 3
+    data = synth_layer(9950, m, n, N, b, k, "bf16", 0.005)
+    res = run_layer(data, "bf16")
+    dev = res["dev"]
+    dR = torch.full_like(dev["th_R"], 0.25)
+    dP = torch.full_like(dev["th_P"], -0.5)
+    lib.poetx_linear_bwd_skew(dev["desc"], dev["X"], dev["dZ"], dev["B"], dev["dA"], dev["pi_R"], dev["pi_P"],
+                              dev["th_R"], dev["th_P"], dR, dP, True, dev["ws"])
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(dR), (torch.from_numpy(res["dtheta_R"]).float() + 0.25).double().numpy())
+    assert np.array_equal(to_np(dP), (torch.from_numpy(res["dtheta_P"]).float() - 0.5).double().numpy())
