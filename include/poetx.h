@@ -147,6 +147,19 @@ size_t poetx_cnp_workspace_bytes(int32_t d, int32_t b);
 int poetx_cnp_build(const float* theta, int32_t d, int32_t b, int32_t k, int32_t precision,
                     float* G_f32, void* E_bf16, void* ws, size_t ws_bytes, void* stream);
 
+/* The same call for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): it takes no workspace and calls no
+ * allocating routine.  The scratch is an array inside the library, resident on every GPU the
+ * library runs on until the process ends (12 * POETX_CNP_STATIC_MAX_ELEMS bytes = 48 MiB); its
+ * per-device address is looked up on the first call on that device.  Requests with
+ * ceil(d/b) * b * b > POETX_CNP_STATIC_MAX_ELEMS return POETX_ERR_UNSUPPORTED.  All calls on one
+ * GPU share that GPU's array (it keeps the last call's contents; the kernels write every element
+ * before reading it, so nothing is cleared): calls that overlap in time on one GPU race -- keep
+ * them on one stream or order them yourself.  Results are those of poetx_cnp_build bit for bit. */
+#define POETX_CNP_STATIC_MAX_ELEMS (1u << 22)   /* e.g. d = 16384 at b = 256, d = 8192 at b = 512 */
+int poetx_cnp_build_static(const float* theta, int32_t d, int32_t b, int32_t k, int32_t precision,
+                           float* G_f32, void* E_bf16, void* stream);
+
 /* ---------------------------------------------------------------------------
  * INT8 codes of a base weight (Sec. 3.6; scheme and buffer layout: see POETX_FLAG_W_INT8).
  * W: n x m in `dtype`.  Wq: poetx_weight_q8_bytes(n, m) bytes (out of quantize, in of

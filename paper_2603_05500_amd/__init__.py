@@ -22,7 +22,7 @@ FLAG_W_INT8 = 2
 
 EXPORTS = (
     "poetx_status_string", "poetx_version", "poetx_debug_force_fma",
-    "poetx_cnp_workspace_bytes", "poetx_cnp_build",
+    "poetx_cnp_workspace_bytes", "poetx_cnp_build", "poetx_cnp_build_static",
     "poetx_perm_blockdiag_apply_left", "poetx_perm_blockdiag_apply_right", "poetx_perm_validate",
     "poetx_linear_workspace_bytes", "poetx_linear_fwd", "poetx_linear_bwd_input", "poetx_linear_bwd_skew",
     "poetx_linear_recompute_b",
@@ -67,6 +67,8 @@ def load_library(path: str | None = None):
     lib.poetx_cnp_build.restype = c_int
     lib.poetx_cnp_build.argtypes = [c_void_p, c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p,
                                     c_void_p, c_size_t, c_void_p]
+    lib.poetx_cnp_build_static.restype = c_int
+    lib.poetx_cnp_build_static.argtypes = [c_void_p, c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p]
     for name in ("poetx_perm_blockdiag_apply_left",):
         f = getattr(lib, name)
         f.restype = c_int
@@ -159,6 +161,12 @@ def poetx_cnp_build(theta, d, b, k, precision, G_f32=None, E_bf16=None, ws=None)
     _check(lib.poetx_cnp_build(_ptr(theta), d, b, k, precision, _ptr(G_f32), _ptr(E_bf16), _ptr(ws),
                                ws.numel() * ws.element_size() if ws is not None else 0, _stream()),
            "poetx_cnp_build")
+
+
+def poetx_cnp_build_static(theta, d, b, k, precision, G_f32=None, E_bf16=None):
+    lib = load_library()
+    _check(lib.poetx_cnp_build_static(_ptr(theta), d, b, k, precision, _ptr(G_f32), _ptr(E_bf16), _stream()),
+           "poetx_cnp_build_static")
 
 
 def poetx_perm_blockdiag_apply_left(V, out, perm, blocks, b, transpose_G):

@@ -2,6 +2,7 @@
 // Every step of the path runs in the kernels of this library; this file only
 // validates, carves the workspace and enqueues.
 #include <atomic>
+#include <mutex>
 
 #include "poetx_kernels.h"
 
@@ -10,6 +11,30 @@ using namespace poetx;
 namespace {
 
 std::atomic<int> g_force_fma{0};
+
+// ---- scratch of the entry point that allocates nothing (poetx_cnp_build_static) ------------
+// One copy of this array lives on every GPU the library runs on, for as long as the process
+// lives.  Its name is only a host-side handle: kernels get the per-device address that
+// hipGetSymbolAddress returns, looked up once per device with that device current.
+constexpr size_t kStaticCnpElems = POETX_CNP_STATIC_MAX_ELEMS;           // block elements: ceil(d/b) * b * b
+constexpr size_t kStaticCnpBytes = 12 * kStaticCnpElems;                 // poetx_cnp_workspace_bytes per element
+static __device__ __align__(256) unsigned char scratch[kStaticCnpBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return POETX_ERR_HIP;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return POETX_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return POETX_OK;
+}
 
 inline bool use_mfma(int dtype) { return dtype == POETX_BF16 && !g_force_fma.load(); }
 inline size_t esize(int dtype) { return dtype == POETX_F32 ? 4 : 2; }
@@ -107,6 +132,19 @@ int poetx_cnp_build(const float* theta, int32_t d, int32_t b, int32_t k, int32_t
   else
     fma_cnp_build(theta, d, b, k, G_f32, E_bf16, (float*)ws, st);
   return launch_status();
+}
+
+int poetx_cnp_build_static(const float* theta, int32_t d, int32_t b, int32_t k, int32_t precision, float* G_f32,
+                           void* E_bf16, void* stream) {
+  if (!theta || (!G_f32 && !E_bf16) || d <= 0 || b <= 0 || k < 1) return POETX_ERR_INVALID_ARG;
+  if (precision != POETX_CNP_FP32 && precision != POETX_CNP_BF16) return POETX_ERR_INVALID_ARG;
+  if (b > d) return POETX_ERR_BAD_SHAPE;
+  if ((size_t)ceil_div(d, b) * b * b > kStaticCnpElems) return POETX_ERR_UNSUPPORTED;   // beyond the static scratch
+  void* ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc != POETX_OK) return rc;
+  // every scratch element the kernels read was written earlier in the same call: nothing to clear
+  return poetx_cnp_build(theta, d, b, k, precision, G_f32, E_bf16, ws, kStaticCnpBytes, stream);
 }
 
 size_t poetx_weight_q8_bytes(int32_t n, int32_t m) {
