@@ -31,6 +31,30 @@ def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     return float(np.max(np.abs(got - ref)) / denom)
 
 
+def row_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """Scale-aware companion of rel_err: the worst row, each row measured on its own scale
+    (max |got_row - ref_row| / max |ref_row|).  A row (a feature across tokens, a block of
+    packed parameters) that is wrong as a whole cannot hide behind larger rows."""
+    got2 = got.reshape(got.shape[0], -1)
+    ref2 = ref.reshape(ref.shape[0], -1)
+    den = np.max(np.abs(ref2), axis=1)
+    num = np.max(np.abs(got2 - ref2), axis=1)
+    ok = den > 0
+    if not ok.any():
+        return float(np.max(num))
+    return float(np.max(num[ok] / den[ok]))
+
+
+def p999_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """99.9th percentile of the element-wise relative error, with the denominator floored at
+    1e-3 of the tensor's largest magnitude (reported next to the tolerance's metric)."""
+    floor = 1e-3 * np.max(np.abs(ref))
+    if floor == 0:
+        return 0.0
+    e = np.abs(got - ref) / np.maximum(np.abs(ref), floor)
+    return float(np.quantile(e.ravel(), 0.999))
+
+
 def ws_tensor(nbytes: int) -> torch.Tensor:
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
 

@@ -7,7 +7,7 @@ import torch
 
 from oracle import poetx_oracle as orc
 from workloads import get_config, draw_projection, round_bf16, round_f32
-from tests.harness import TOL, build_blocks, rel_err, run_layer, tdtype, to_dev, to_np, ws_tensor
+from tests.harness import TOL, build_blocks, rel_err, row_rel_err, run_layer, tdtype, to_dev, to_np, ws_tensor
 
 pytestmark = pytest.mark.gpu
 RNG = lambda s: np.random.Generator(np.random.PCG64(s))
@@ -145,17 +145,20 @@ def test_perm_validate(lib):
 
 # ------------------------------------------------------------------ whole layer, configs 1 and 2
 def check_layer(res, ref, pi_P, dtype):
+    """Every output against the oracle: on the tensor's scale (the tolerance's metric) and row by row
+    (a feature across tokens / a block of packed parameters on its own scale).  The blocks are
+    compared on the scale of G - I: G itself is dominated by the identity."""
     tol = TOL[dtype]
     errs = {}
     B_ref = np.empty_like(ref["Bp"])
     B_ref[pi_P, :] = ref["Bp"]  # the library keeps B in physical feature order
-    errs["G_R"] = rel_err(res["G_R"], ref["G_R"])
-    errs["G_P"] = rel_err(res["G_P"], ref["G_P"])
-    errs["Z"] = rel_err(res["Z"], ref["Z"])
-    errs["B"] = rel_err(res["B"], B_ref)
-    errs["dX"] = rel_err(res["dX"], ref["dX"])
-    errs["dtheta_R"] = rel_err(res["dtheta_R"], ref["dtheta_R"])
-    errs["dtheta_P"] = rel_err(res["dtheta_P"], ref["dtheta_P"])
+    eye = np.eye(ref["G_R"].shape[-1])
+    pairs = {"G_R-I": (res["G_R"] - eye, ref["G_R"] - eye), "G_P-I": (res["G_P"] - eye, ref["G_P"] - eye),
+             "Z": (res["Z"], ref["Z"]), "B": (res["B"], B_ref), "dX": (res["dX"], ref["dX"]),
+             "dtheta_R": (res["dtheta_R"], ref["dtheta_R"]), "dtheta_P": (res["dtheta_P"], ref["dtheta_P"])}
+    for key, (got, want) in pairs.items():
+        errs[key] = rel_err(got, want)
+        errs["row " + key] = row_rel_err(got, want)
     bad = {k: v for k, v in errs.items() if not v <= tol}
     assert not bad, f"over tolerance {tol}: {bad} (all: {errs})"
     return errs
@@ -183,6 +186,35 @@ def test_config2_bf16_layer(lib, proj):
         r = orc.tail_side(d, data["b"])
         if r < data["b"]:
             iu, ju = np.triu_indices(data["b"], k=1)
+            assert np.all(res[side][-1, (iu >= r) | (ju >= r)] == 0)
+
+
+@pytest.mark.parametrize("proj", [4, 6])   # gate: ragged output side; down: ragged input side
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_config2_dead_slots_of_the_tail_block_are_ignored(lib, proj, dtype):
+    """The packed parameters of a ragged tail block keep b(b-1)/2 slots; those with an index beyond
+    the tail side hold arbitrary non-zero values here.  Forward, input gradient and parameter
+    gradients must not see them, and their own gradient must be exactly zero."""
+    cfg = get_config(2)
+    data = draw_projection(cfg, proj, zero_dead=False)
+    b = data["b"]
+    iu, ju = np.triu_indices(b, k=1)
+    for side, d in (("theta_R", data["m"]), ("theta_P", data["n"])):
+        r = orc.tail_side(d, b)
+        if r < b:
+            dead = (iu >= r) | (ju >= r)
+            data[side][-1, dead] = round_f32(RNG(77 + proj).standard_normal(dead.sum()) * 3.0 + 5.0)   # loud
+            assert np.all(data[side][-1, dead] != 0)
+    if dtype == "f32":
+        for key in ("X", "dZ", "W"):
+            data[key] = round_f32(data[key])
+    res = run_layer(data, dtype)
+    ref = orc.linear_fwd_bwd_from_theta(data["X"], data["dZ"], data["W"], data["pi_R"], data["pi_P"],
+                                        data["theta_R"], data["theta_P"], b, data["k"])
+    check_layer(res, ref, data["pi_P"], dtype)
+    for side, d in (("dtheta_R", data["m"]), ("dtheta_P", data["n"])):
+        r = orc.tail_side(d, b)
+        if r < b:
             assert np.all(res[side][-1, (iu >= r) | (ju >= r)] == 0)
 
 
@@ -248,6 +280,23 @@ def test_on_chip_series_orders(lib, k):
     check_layer(res, ref, data["pi_P"], "bf16")
 
 
+@pytest.mark.parametrize("k", [1, 2, 3])
+@pytest.mark.parametrize("b,dtype", [(32, "f32"), (64, "bf16"), (256, "bf16")])
+def test_plain_series_orders(lib, k, b, dtype):
+    """The plain fp32 series kernels (fp32 tensors, small blocks, and bf16 tensors forced onto them) at
+    the short orders: k = 1 runs no intermediate Horner step, k = 2 exactly one."""
+    m, n, N = 3 * b, 2 * b, 128
+    data = synth_layer(7350 + 10 * k + b, m, n, N, b, k, dtype, 0.01)
+    ref = orc.linear_fwd_bwd_from_theta(data["X"], data["dZ"], data["W"], data["pi_R"], data["pi_P"],
+                                        data["theta_R"], data["theta_P"], b, k)
+    lib.poetx_debug_force_fma(True)
+    try:
+        res = run_layer(data, dtype, cnp_precision=lib.CNP_FP32)
+    finally:
+        lib.poetx_debug_force_fma(False)
+    check_layer(res, ref, data["pi_P"], dtype)
+
+
 @pytest.mark.parametrize("N", [64, 128, 192, 320, 384, 576])
 def test_kernel_family_boundaries(lib, N):
     """Token counts around the tile sizes of the matrix-core kernels (128-token apply tiles, 256-token
@@ -292,8 +341,8 @@ def test_merge_step(lib, m, n, b, dtype):
 # ------------------------------------------------------------------ memory-saving variant
 @pytest.mark.parametrize("m,n,N,b,k,dtype", [(512, 256, 512, 256, 4, "bf16"), (256, 256, 512, 32, 4, "f32")])
 def test_mem_variant_matches_fast(lib, m, n, N, b, k, dtype):
-    """POET-X_mem: no saved activation in forward, B recomputed in backward -- same kernels, so the
-    outputs must equal the fast variant bit for bit (and the fast variant is checked against the oracle)."""
+    """POET-X_mem: no saved activation in forward, B recomputed in backward.  Its outputs are checked
+    against the oracle, and -- same kernels -- must equal the fast variant bit for bit."""
     data = synth_layer(9500 + m + n, m, n, N, b, k, dtype)
     fast = run_layer(data, dtype)
     dev = fast["dev"]
@@ -311,6 +360,13 @@ def test_mem_variant_matches_fast(lib, m, n, N, b, k, dtype):
     lib.poetx_linear_bwd_skew(desc, dev["X"], dev["dZ"], B, dA, dev["pi_R"], dev["pi_P"], dev["th_R"], dev["th_P"],
                               dR, dP, False, ws)
     torch.cuda.synchronize()
+    # against the oracle, on its own: forward, recomputed activation, both backward halves
+    ref = orc.linear_fwd_bwd_from_theta(data["X"], data["dZ"], data["W"], data["pi_R"], data["pi_P"],
+                                        data["theta_R"], data["theta_P"], b, k)
+    mem = {"G_R": fast["G_R"], "G_P": fast["G_P"], "Z": to_np(Z), "B": to_np(B), "dX": to_np(dX),
+           "dtheta_R": to_np(dR), "dtheta_P": to_np(dP)}
+    check_layer(mem, ref, data["pi_P"], dtype)
+    # and the same kernels as the fast variant, so bit for bit the same values
     assert torch.equal(Z, dev["Z"]) and torch.equal(B, dev["B"]) and torch.equal(dX, dev["dX"])
     assert np.array_equal(to_np(dR), fast["dtheta_R"]) and np.array_equal(to_np(dP), fast["dtheta_P"])
     # without the flag a missing saved_B is refused on the host

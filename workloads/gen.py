@@ -43,19 +43,20 @@ def _normal(shape, sigma, seed):
     return g.standard_normal(shape) * sigma
 
 
-def draw_theta(d: int, b: int, sigma: float, seed: int) -> np.ndarray:
-    """Packed skew parameters, fp32-rounded; unused slots of a ragged tail block are zero."""
+def draw_theta(d: int, b: int, sigma: float, seed: int, zero_dead: bool = True) -> np.ndarray:
+    """Packed skew parameters, fp32-rounded.  The unused slots of a ragged tail block are zero
+    unless zero_dead is False (they must be ignored either way; the non-zero draw checks that)."""
     nb, L = theta_shape(d, b)
     th = round_f32(_normal((nb, L), sigma, seed))
     r = d - b * (nb - 1)
-    if r < b:
+    if r < b and zero_dead:
         iu, ju = np.triu_indices(b, k=1)
         th[nb - 1, (iu >= r) | (ju >= r)] = 0.0
     return th
 
 
 def draw_projection(cfg, proj_index: int, n_tokens: int | None = None, step: int = 0,
-                    want=("X", "dZ", "W", "theta_R", "theta_P", "pi_R", "pi_P")) -> dict:
+                    want=("X", "dZ", "W", "theta_R", "theta_P", "pi_R", "pi_P"), zero_dead: bool = True) -> dict:
     """All tensors of one projection of `cfg` (feature-major: X is m x N, dZ is n x N)."""
     p = cfg.projections[proj_index]
     N = cfg.n_tokens if n_tokens is None else n_tokens
@@ -70,9 +71,9 @@ def draw_projection(cfg, proj_index: int, n_tokens: int | None = None, step: int
     if "W" in want:
         out["W"] = rnd(_normal((n, m), cfg.sigma_w, tensor_seed(ci, proj_index, T_W)))
     if "theta_R" in want:
-        out["theta_R"] = draw_theta(m, b, cfg.sigma_theta, tensor_seed(ci, proj_index, T_THETA_R))
+        out["theta_R"] = draw_theta(m, b, cfg.sigma_theta, tensor_seed(ci, proj_index, T_THETA_R), zero_dead)
     if "theta_P" in want:
-        out["theta_P"] = draw_theta(n, b, cfg.sigma_theta, tensor_seed(ci, proj_index, T_THETA_P))
+        out["theta_P"] = draw_theta(n, b, cfg.sigma_theta, tensor_seed(ci, proj_index, T_THETA_P), zero_dead)
     if "pi_R" in want:
         out["pi_R"] = draw_permutation(m, tensor_seed(ci, proj_index, T_PI_R, step))
     if "pi_P" in want:
