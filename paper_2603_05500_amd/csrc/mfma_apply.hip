@@ -207,24 +207,27 @@ __global__ __launch_bounds__(512) void apply_left_stream_kernel(const uint16_t* 
       fragB[c2] = k * (BN * 2) + 16 * mm::kx_chunk<BN>(c, k) + 8 * (i & 1);
     }
   }
-  // store offsets: own row, tokens c*32 + 8q + 4h
-  const i64 soff = (i64)pm[row_own] * ld + tok0 + 4 * h;
+  // store offsets: own row; after the lane-half swap a lane owns tokens c*32 + 16p + 8h + 0..7
+  const i64 soff = (i64)pm[row_own] * ld + tok0 + 8 * h;
 
   // The packed results of a tile are stored one iteration late, right after the next barrier:
   // by the following barrier both those stores and the loads of the next tile are old, so a
   // plain vmcnt(0) there waits for nothing that is not already due (loads and stores share
   // one counter and may retire out of order with respect to each other).
-  uint2 pend[TN * 4];
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 pend[TN * 2];
   auto flush = [&](int t) {
     uint16_t* o = out + soff + (i64)t * BN;
 #pragma unroll
     for (int c = 0; c < TN; ++c)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) *reinterpret_cast<uint2*>(o + c * 32 + 8 * q) = pend[c * 4 + q];
+      for (int p = 0; p < 2; ++p) *reinterpret_cast<u32x4*>(o + c * 32 + 16 * p) = pend[c * 2 + p];
   };
   for (int t = 0; t < tiles_per_wg; ++t) {
-    // tile t has landed and every wave is done reading the stage that tile t+1 overwrites
-    mm::wait_vmcnt_and_barrier<0>();
+    // tile t has landed and every wave is done reading the stage that tile t+1 overwrites: the
+    // wait covers this wave's own LDS reads too (lgkmcnt), so the ring does not depend on where the
+    // compiler places the MFMAs that consume them
+    mm::wait_all_reads_and_barrier<0>();
     if (t > 0) flush(t - 1);
     if (t + 1 < tiles_per_wg) issue(t + 1);
     const char* stage = ring + (t & 1) * STAGE_BYTES;
@@ -261,13 +264,22 @@ __global__ __launch_bounds__(512) void apply_left_stream_kernel(const uint16_t* 
       for (int c = 0; c < TN; ++c)
         acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks & 1][c], fa[ks], acc[c], 0, 0, 0);
     }
+    // round; registers 4q..4q+3 hold tokens 8q + 4h + 0..3.  v_permlane32_swap exchanges the upper
+    // lane half of its first operand with the lower half of its second, which leaves the lower lanes
+    // with tokens 16p .. 16p+7 and the upper lanes with tokens 16p+8 .. 16p+15: 16-byte stores
 #pragma unroll
-    for (int c = 0; c < TN; ++c)
+    for (int c = 0; c < TN; ++c) {
+      uint32_t w[8];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        pend[c * 4 + q].x = mm::pack2_bf16(acc[c][4 * q + 0], acc[c][4 * q + 1]);
-        pend[c * 4 + q].y = mm::pack2_bf16(acc[c][4 * q + 2], acc[c][4 * q + 3]);
+      for (int e = 0; e < 8; ++e) w[e] = mm::pack2_bf16(acc[c][2 * e], acc[c][2 * e + 1]);
+#pragma unroll
+      for (int p = 0; p < 2; ++p) {
+        typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+        const uint2v r0 = __builtin_amdgcn_permlane32_swap(w[4 * p], w[4 * p + 2], false, false);
+        const uint2v r1 = __builtin_amdgcn_permlane32_swap(w[4 * p + 1], w[4 * p + 3], false, false);
+        pend[c * 2 + p] = u32x4{r0[0], r1[0], r0[1], r1[1]};
       }
+    }
   }
   flush(tiles_per_wg - 1);
 }
@@ -301,7 +313,10 @@ void launch_apply_stream(const uint16_t* V, uint16_t* out, int d, i64 cols, i64 
   const int chunks = stream_chunks(nb * MSPLIT, tiles);
   hipLaunchKernelGGL(kern, dim3(chunks * MSPLIT, nb), dim3(512), LDS, st, V, out, ld, perm, E, trans, tiles / chunks);
 }
-constexpr int SBN256 = 128, SBN512 = 64;
+#ifndef SBN256_OVERRIDE
+#define SBN256_OVERRIDE 128
+#endif
+constexpr int SBN256 = SBN256_OVERRIDE, SBN512 = 64;
 
 template <int B, int BN>
 void launch_apply(const uint16_t* V, uint16_t* out, int d, i64 cols, i64 ld, const int32_t* perm, const uint16_t* E,
