@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--variant", default="fast", choices=["fast", "mem", "xq"],
                     help="fast keeps B from the forward pass (the measured metric); mem recomputes it in backward; "
                          "xq is mem on an INT8 base weight that every dense product dequantises first")
+    ap.add_argument("--two-call-backward", action="store_true",
+                    help="run the backward pass as poetx_linear_bwd_input + poetx_linear_bwd_skew instead of the "
+                         "single poetx_linear_bwd call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=128, help="tokens in the oracle's timed sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -260,12 +263,17 @@ def main():
                 px.poetx_cnp_build(p["theta_P"], n, b, k, prec, ws=cws, **kw)
             px.poetx_linear_fwd(p["desc"], p["X"], p["W"], p["pi_R"], p["pi_P"], p["blk_R"], p["blk_P"],
                                 Z[:n], None if args.variant != "fast" else B[:n], ws)
-            px.poetx_linear_bwd_input(p["desc"], p["dZ"], p["W"], p["pi_R"], p["pi_P"], p["blk_R"], p["blk_P"],
-                                      dX[:m], dA[:m], ws)
             if args.variant != "fast":
                 px.poetx_linear_recompute_b(p["desc"], p["X"], p["W"], p["pi_R"], p["blk_R"], B[:n], ws)
-            px.poetx_linear_bwd_skew(p["desc"], p["X"], p["dZ"], B[:n], dA[:m], p["pi_R"], p["pi_P"],
-                                     p["theta_R"], p["theta_P"], p["dtheta_R"], p["dtheta_P"], False, ws)
+            if args.two_call_backward:
+                px.poetx_linear_bwd_input(p["desc"], p["dZ"], p["W"], p["pi_R"], p["pi_P"], p["blk_R"], p["blk_P"],
+                                          dX[:m], dA[:m], ws)
+                px.poetx_linear_bwd_skew(p["desc"], p["X"], p["dZ"], B[:n], dA[:m], p["pi_R"], p["pi_P"],
+                                         p["theta_R"], p["theta_P"], p["dtheta_R"], p["dtheta_P"], False, ws)
+            else:   # the whole backward pass in one call: each side's gradient is streamed once
+                px.poetx_linear_bwd(p["desc"], p["X"], p["dZ"], B[:n], p["W"], p["pi_R"], p["pi_P"], p["blk_R"],
+                                    p["blk_P"], p["theta_R"], p["theta_P"], dX[:m], p["dtheta_R"], p["dtheta_P"],
+                                    False, ws)
         step_no[0] += 1
 
     if args.copy_calibration:
@@ -307,8 +315,12 @@ def main():
     dense_tflops = dense_f * args.steps / (dense_ms * 1e-3) / 1e12 if dense_ms > 0 else 0.0
     # HBM-bound block stages: algorithmic bytes = 2 s N d per apply (4 per projection side pair) ...
     es = 2 if cfg.dtype == "bf16" else 4
-    apply_bytes = sum(4 * es * N * (p["m"] + p["n"]) for p in projs)      # 4 applies: read + write each
-    bgrad_bytes = sum(2 * es * N * (p["m"] + p["n"]) for p in projs)      # 2 reductions: two reads each
+    unit = sum(es * N * (p["m"] + p["n"]) for p in projs)                 # one pass over an activation of each side
+    ag_ms, ag_cnt = stages["apply_grad"]
+    fused = ag_cnt > 0
+    apply_bytes = (2 if fused else 4) * unit      # forward applies (+ backward applies when not fused): read + write
+    bgrad_bytes = 2 * unit                        # separate block gradients: two reads per side
+    ag_bytes = 3 * unit                           # one-pass backward block stage: read V, read U, write out
     apply_ms, _ = stages["apply"]
     bgrad_ms, _ = stages["blockgrad"]
     out = {
@@ -330,6 +342,7 @@ def main():
             "dense_TFLOPs": dense_tflops,
             "apply_GBs": apply_bytes * args.steps / (apply_ms * 1e-3) / 1e9 if apply_ms > 0 else 0.0,
             "blockgrad_GBs": bgrad_bytes * args.steps / (bgrad_ms * 1e-3) / 1e9 if bgrad_ms > 0 else 0.0,
+            "apply_grad_GBs": ag_bytes * args.steps / (ag_ms * 1e-3) / 1e9 if ag_ms > 0 else 0.0,
         },
         "roofline": {"bound": "mfma", "kernel": "dense bf16 product (B = W A, dA = W^T dB)",
                      "achieved": dense_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

@@ -129,7 +129,8 @@ typedef enum {
   POETX_STAGE_DENSE = 2,      /* B = W A and dA = W^T dB                         */
   POETX_STAGE_BLOCKGRAD = 3,  /* per-block token reduction dG                    */
   POETX_STAGE_CNP_BWD = 4,    /* series backward + packed projection             */
-  POETX_STAGE_COUNT = 5
+  POETX_STAGE_APPLY_GRAD = 5, /* poetx_linear_bwd: structured product and block gradient of a side in one pass */
+  POETX_STAGE_COUNT = 6
 } poetx_stage;
 int poetx_profile_begin(int32_t max_records);
 int poetx_profile_end(double* ms_by_stage, int64_t* launches_by_stage);
@@ -200,7 +201,7 @@ int poetx_perm_validate(const int32_t* perm, int32_t d, int32_t* scratch, void* 
  *             dG_P^j = B'_j dZ'_j^T, dG_R^j = X'_j dA'_j^T  (primes: rows
  *             gathered by the side's permutation), then the chain rule through
  *             the series and the projection onto the packed parameters.
- * poetx_linear_workspace_bytes: scratch needed by the largest of the three.
+ * poetx_linear_workspace_bytes: scratch needed by the largest of the linear calls.
  */
 size_t poetx_linear_workspace_bytes(const poetx_linear_desc* desc);
 
@@ -239,6 +240,22 @@ int poetx_linear_bwd_skew(const poetx_linear_desc* desc, const void* X, const vo
                           const float* theta_R, const float* theta_P,
                           float* dtheta_R, float* dtheta_P, int32_t accumulate,
                           void* ws, size_t ws_bytes, void* stream);
+
+/* The whole backward pass in one call (Sec. 3.5, all three bullets, then Sec. 3.4 backward): the
+ * results of poetx_linear_bwd_input followed by poetx_linear_bwd_skew, with dA kept in the workspace.
+ * Where the shapes allow (bf16, b = 256, d_in, d_out multiples of 256, n_tokens a multiple of 256) each
+ * side's gradient is streamed from memory once: dB = P dZ is produced together with
+ * dG_P^j = B'_j dZ'_j^T, and dX = R dA together with dG_R^j = X'_j dA'_j^T, instead of one pass
+ * for the product and another for the block gradient.  Otherwise it runs the two halves as they are.
+ * The block gradients are summed over token ranges in a fixed order, so results are reproducible
+ * run to run; they differ from the two-call results only by that summation order.
+ * Arguments as in the two halves; W follows desc->flags (POETX_FLAG_W_INT8). */
+int poetx_linear_bwd(const poetx_linear_desc* desc, const void* X, const void* dZ, const void* saved_B,
+                     const void* W, const int32_t* perm_R, const int32_t* perm_P,
+                     const void* blocks_R, const void* blocks_P,
+                     const float* theta_R, const float* theta_P,
+                     void* dX, float* dtheta_R, float* dtheta_P, int32_t accumulate,
+                     void* ws, size_t ws_bytes, void* stream);
 
 #ifdef __cplusplus
 }

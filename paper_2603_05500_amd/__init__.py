@@ -25,11 +25,11 @@ EXPORTS = (
     "poetx_cnp_workspace_bytes", "poetx_cnp_build", "poetx_cnp_build_static",
     "poetx_perm_blockdiag_apply_left", "poetx_perm_blockdiag_apply_right", "poetx_perm_validate",
     "poetx_linear_workspace_bytes", "poetx_linear_fwd", "poetx_linear_bwd_input", "poetx_linear_bwd_skew",
-    "poetx_linear_recompute_b",
+    "poetx_linear_recompute_b", "poetx_linear_bwd",
     "poetx_weight_q8_bytes", "poetx_weight_quantize_q8", "poetx_weight_dequantize_q8",
     "poetx_profile_begin", "poetx_profile_end",
 )
-STAGES = ("cnp_fwd", "apply", "dense", "blockgrad", "cnp_bwd")
+STAGES = ("cnp_fwd", "apply", "dense", "blockgrad", "cnp_bwd", "apply_grad")
 
 
 class LinearDesc(Structure):
@@ -88,6 +88,8 @@ def load_library(path: str | None = None):
     lib.poetx_linear_bwd_skew.restype = c_int
     lib.poetx_linear_bwd_skew.argtypes = [POINTER(LinearDesc)] + [c_void_p] * 10 + [c_int32, c_void_p, c_size_t,
                                                                                    c_void_p]
+    lib.poetx_linear_bwd.restype = c_int
+    lib.poetx_linear_bwd.argtypes = [POINTER(LinearDesc)] + [c_void_p] * 13 + [c_int32, c_void_p, c_size_t, c_void_p]
     lib.poetx_linear_recompute_b.restype = c_int
     lib.poetx_linear_recompute_b.argtypes = [POINTER(LinearDesc)] + [c_void_p] * 6 + [c_size_t, c_void_p]
     lib.poetx_weight_q8_bytes.restype = c_size_t
@@ -228,6 +230,16 @@ def poetx_linear_bwd_skew(desc, X, dZ, saved_B, dA, perm_R, perm_P, theta_R, the
                                      _ptr(perm_P), _ptr(theta_R), _ptr(theta_P), _ptr(dtheta_R), _ptr(dtheta_P),
                                      int(bool(accumulate)), _ptr(ws), _ws_bytes(ws), _stream()),
            "poetx_linear_bwd_skew")
+
+
+def poetx_linear_bwd(desc, X, dZ, saved_B, W, perm_R, perm_P, blocks_R, blocks_P, theta_R, theta_P, dX,
+                     dtheta_R, dtheta_P, accumulate, ws):
+    lib = load_library()
+    _check(lib.poetx_linear_bwd(ctypes.byref(desc), _ptr(X), _ptr(dZ), _ptr(saved_B), _ptr(W), _ptr(perm_R),
+                                _ptr(perm_P), _ptr(blocks_R), _ptr(blocks_P), _ptr(theta_R), _ptr(theta_P),
+                                _ptr(dX), _ptr(dtheta_R), _ptr(dtheta_P), int(bool(accumulate)), _ptr(ws),
+                                _ws_bytes(ws), _stream()),
+           "poetx_linear_bwd")
 
 
 def poetx_weight_q8_bytes(n: int, m: int) -> int:

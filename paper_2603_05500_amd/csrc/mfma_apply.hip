@@ -207,21 +207,37 @@ __global__ __launch_bounds__(512) void apply_left_stream_kernel(const uint16_t* 
       fragB[c2] = k * (BN * 2) + 16 * mm::kx_chunk<BN>(c, k) + 8 * (i & 1);
     }
   }
-  // store offsets: own row; after the lane-half swap a lane owns tokens c*32 + 16p + 8h + 0..7
-  const i64 soff = (i64)pm[row_own] * ld + tok0 + 8 * h;
+  // Results leave through a per-wave staging area behind the ring (32 rows x 64 tokens = 4 KB): the
+  // wave writes a 64-token half of its tile there in accumulator order and reads it back with 8
+  // consecutive lanes on one row, so that every global store instruction writes whole 128-byte row
+  // segments (scattered through the same index map that gathered the rows).  Only the wave itself
+  // touches its area, so its own lgkmcnt wait is all the synchronisation this needs.
+  constexpr int NH = TN / 2;                          // 64-token halves of a tile
+  char* stg = ring + 2 * STAGE_BYTES + wave * 4096;
+  // write side: row li, chunk (8 tokens) cl*4 + 2p + h of the half, XOR-swizzled by the row pair
+  const int stg_w = li * 128 + 16 * (h ^ ((li >> 1) & 7));
+  // read side / stores: rows (lane >> 3) + 8 i, chunk lane & 7
+  i64 soff[4];
+  int stg_r[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = (lane >> 3) + 8 * i;
+    soff[i] = (i64)pm[slice * 256 + wave * 32 + r] * ld + tok0 + 8 * (lane & 7);
+    stg_r[i] = r * 128 + 16 * ((lane & 7) ^ ((r >> 1) & 7));
+  }
 
-  // The packed results of a tile are stored one iteration late, right after the next barrier:
-  // by the following barrier both those stores and the loads of the next tile are old, so a
-  // plain vmcnt(0) there waits for nothing that is not already due (loads and stores share
-  // one counter and may retire out of order with respect to each other).
+  // The stores of a tile are issued one iteration late, right after the next barrier: by the
+  // following barrier both those stores and the loads of the next tile are old, so a plain
+  // vmcnt(0) there waits for nothing that is not already due (loads and stores share one counter
+  // and may retire out of order with respect to each other).
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-  u32x4 pend[TN * 2];
+  u32x4 pend[NH * 4];
   auto flush = [&](int t) {
-    uint16_t* o = out + soff + (i64)t * BN;
 #pragma unroll
-    for (int c = 0; c < TN; ++c)
+    for (int hf = 0; hf < NH; ++hf)
 #pragma unroll
-      for (int p = 0; p < 2; ++p) *reinterpret_cast<u32x4*>(o + c * 32 + 16 * p) = pend[c * 2 + p];
+      for (int i = 0; i < 4; ++i)
+        *reinterpret_cast<u32x4*>(out + soff[i] + (i64)t * BN + hf * 64) = pend[hf * 4 + i];
   };
   for (int t = 0; t < tiles_per_wg; ++t) {
     // tile t has landed and every wave is done reading the stage that tile t+1 overwrites: the
@@ -266,19 +282,29 @@ __global__ __launch_bounds__(512) void apply_left_stream_kernel(const uint16_t* 
     }
     // round; registers 4q..4q+3 hold tokens 8q + 4h + 0..3.  v_permlane32_swap exchanges the upper
     // lane half of its first operand with the lower half of its second, which leaves the lower lanes
-    // with tokens 16p .. 16p+7 and the upper lanes with tokens 16p+8 .. 16p+15: 16-byte stores
+    // with tokens 16p .. 16p+7 and the upper lanes with tokens 16p+8 .. 16p+15 of the 32-token
+    // tile: 16-byte pieces, written to the staging area and read back row by row
 #pragma unroll
-    for (int c = 0; c < TN; ++c) {
-      uint32_t w[8];
+    for (int hf = 0; hf < NH; ++hf) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) w[e] = mm::pack2_bf16(acc[c][2 * e], acc[c][2 * e + 1]);
+      for (int cl = 0; cl < 2; ++cl) {
+        const int c = 2 * hf + cl;
+        uint32_t w[8];
 #pragma unroll
-      for (int p = 0; p < 2; ++p) {
-        typedef unsigned uint2v __attribute__((ext_vector_type(2)));
-        const uint2v r0 = __builtin_amdgcn_permlane32_swap(w[4 * p], w[4 * p + 2], false, false);
-        const uint2v r1 = __builtin_amdgcn_permlane32_swap(w[4 * p + 1], w[4 * p + 3], false, false);
-        pend[c * 2 + p] = u32x4{r0[0], r1[0], r0[1], r1[1]};
+        for (int e = 0; e < 8; ++e) w[e] = mm::pack2_bf16(acc[c][2 * e], acc[c][2 * e + 1]);
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+          typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+          const uint2v r0 = __builtin_amdgcn_permlane32_swap(w[4 * p], w[4 * p + 2], false, false);
+          const uint2v r1 = __builtin_amdgcn_permlane32_swap(w[4 * p + 1], w[4 * p + 3], false, false);
+          // chunk cl*4 + 2p + h: the XOR with the row pair commutes with adding the even part
+          *reinterpret_cast<u32x4*>(stg + (stg_w ^ (16 * (cl * 4 + 2 * p)))) = u32x4{r0[0], r1[0], r0[1], r1[1]};
+        }
       }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int i = 0; i < 4; ++i) pend[hf * 4 + i] = *reinterpret_cast<const u32x4*>(stg + stg_r[i]);
+      if (hf + 1 < NH) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // read back before the area is rewritten
     }
   }
   flush(tiles_per_wg - 1);
@@ -301,7 +327,7 @@ int stream_chunks(int slices, int tiles) {
 template <int B, int BN>
 void launch_apply_stream(const uint16_t* V, uint16_t* out, int d, i64 cols, i64 ld, const int32_t* perm,
                          const uint16_t* E, int trans, hipStream_t st) {
-  constexpr size_t LDS = 2 * (size_t)B * BN * 2;
+  constexpr size_t LDS = 2 * (size_t)B * BN * 2 + 8 * 4096;   // 2-stage ring + per-wave output staging
   constexpr int MSPLIT = B / 256;
   auto kern = apply_left_stream_kernel<B, BN>;
   static bool configured = false;

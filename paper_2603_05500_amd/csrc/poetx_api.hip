@@ -224,7 +224,22 @@ size_t poetx_linear_workspace_bytes(const poetx_linear_desc* desc) {
   if (both > chain) chain = both;
   size_t skew = align256(chain * sizeof(float)) + (bg_in > bg_out ? bg_in : bg_out);
   size_t w = fwd > bwi ? fwd : bwi;
-  return w > skew ? w : skew;
+  if (skew > w) w = skew;
+  // poetx_linear_bwd keeps dA (and, on its one-pass path, dB) in the workspace next to what the two
+  // halves need: dA | two-call scratch, or dA | dB | dG + chain | partials or dequantised weight
+  const size_t two_calls = bwi > skew ? bwi : skew;
+  size_t bwd = align256((size_t)desc->d_in * N * es) + two_calls;
+  if (desc->dtype == POETX_BF16 && mfma_apply_grad_supported(desc->d_in, desc->n_tokens, desc->n_tokens, desc->block) &&
+      mfma_apply_grad_supported(desc->d_out, desc->n_tokens, desc->n_tokens, desc->block)) {
+    size_t tail = align256(mfma_apply_grad_workspace_bytes(desc->d_in, desc->n_tokens));
+    const size_t po = align256(mfma_apply_grad_workspace_bytes(desc->d_out, desc->n_tokens));
+    if (po > tail) tail = po;
+    if (wdeq > tail) tail = wdeq;
+    const size_t one_pass = align256((size_t)desc->d_in * N * es) + align256((size_t)desc->d_out * N * es) +
+                            align256(chain * sizeof(float)) + tail;
+    if (one_pass > bwd) bwd = one_pass;
+  }
+  return w > bwd ? w : bwd;
 }
 
 int poetx_linear_fwd(const poetx_linear_desc* desc, const void* X, const void* W, const int32_t* perm_R,
@@ -266,14 +281,10 @@ int poetx_linear_recompute_b(const poetx_linear_desc* desc, const void* X, const
   return launch_status();
 }
 
-int poetx_linear_bwd_input(const poetx_linear_desc* desc, const void* dZ, const void* W, const int32_t* perm_R,
+// dB = P dZ, dA = W^T dB, dX = R dA; ws holds dB (and the dequantised weight behind it)
+static void bwd_input_impl(const poetx_linear_desc* desc, const void* dZ, const void* W, const int32_t* perm_R,
                            const int32_t* perm_P, const void* blocks_R, const void* blocks_P, void* dX, void* dA,
-                           void* ws, size_t ws_bytes, void* stream) {
-  int rc = check_desc(desc);
-  if (rc) return rc;
-  if (!dZ || !W || !perm_R || !perm_P || !blocks_R || !blocks_P || !dX || !dA) return POETX_ERR_INVALID_ARG;
-  if (!ws || ws_bytes < poetx_linear_workspace_bytes(desc)) return POETX_ERR_WORKSPACE;
-  hipStream_t st = (hipStream_t)stream;
+                           void* ws, hipStream_t st) {
   const int m = desc->d_in, n = desc->d_out, b = desc->block, dt = desc->dtype;
   const i64 N = desc->n_tokens;
   void* dB = ws;
@@ -281,19 +292,39 @@ int poetx_linear_bwd_input(const poetx_linear_desc* desc, const void* dZ, const 
   apply_left_dispatch(dt, dZ, dB, n, N, N, perm_P, blocks_P, b, 0, st);  // dB = P dZ
   dense_dispatch(dt, 1, W, n, m, dB, dA, N, st);                        // dA = W^T dB
   apply_left_dispatch(dt, dA, dX, m, N, N, perm_R, blocks_R, b, 0, st);  // dX = R dA
+}
+
+int poetx_linear_bwd_input(const poetx_linear_desc* desc, const void* dZ, const void* W, const int32_t* perm_R,
+                           const int32_t* perm_P, const void* blocks_R, const void* blocks_P, void* dX, void* dA,
+                           void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (!dZ || !W || !perm_R || !perm_P || !blocks_R || !blocks_P || !dX || !dA) return POETX_ERR_INVALID_ARG;
+  if (!ws || ws_bytes < poetx_linear_workspace_bytes(desc)) return POETX_ERR_WORKSPACE;
+  bwd_input_impl(desc, dZ, W, perm_R, perm_P, blocks_R, blocks_P, dX, dA, ws, (hipStream_t)stream);
   return launch_status();
 }
 
-int poetx_linear_bwd_skew(const poetx_linear_desc* desc, const void* X, const void* dZ, const void* saved_B,
+// Series backward of both sides as one batch on the on-chip chains (b = 256): dG holds the block
+// gradients of the P side, then of the R side; Qb and chain are scratch behind it.
+static void cnp_bwd_both_on_chip(const float* theta_R, const float* theta_P, float* dG, int m, int n, int b, int k,
+                                 float* dtheta_R, float* dtheta_P, int accumulate, hipStream_t st) {
+  const int nbP = n / b, nbR = m / b, nbt = nbP + nbR;
+  const size_t bb = (size_t)b * b;
+  uint16_t* Qb = (uint16_t*)(dG + nbt * bb);                // [nbt][b][b] bf16 (one float slot per element)
+  float* chain = dG + 2 * nbt * bb;                         // (k + 1) * nbt * b * b floats
+  StageTimer tm(POETX_STAGE_CNP_BWD, st);
+  skew_materialize_launch(theta_P, b, nbP, nullptr, Qb, nullptr, st);
+  skew_materialize_launch(theta_R, b, nbR, nullptr, Qb + nbP * bb, nullptr, st);
+  const float* dQ = lds_cnp_bwd_chain(Qb, dG, nbt, k, chain, st);
+  skew_project_launch(dQ, b, n, dtheta_P, accumulate != 0, st);
+  skew_project_launch(dQ + nbP * bb, b, m, dtheta_R, accumulate != 0, st);
+}
+
+static void bwd_skew_impl(const poetx_linear_desc* desc, const void* X, const void* dZ, const void* saved_B,
                           const void* dA, const int32_t* perm_R, const int32_t* perm_P, const float* theta_R,
                           const float* theta_P, float* dtheta_R, float* dtheta_P, int32_t accumulate, void* ws,
-                          size_t ws_bytes, void* stream) {
-  int rc = check_desc(desc);
-  if (rc) return rc;
-  if (!X || !dZ || !saved_B || !dA || !perm_R || !perm_P || !theta_R || !theta_P || !dtheta_R || !dtheta_P)
-    return POETX_ERR_INVALID_ARG;
-  if (!ws || ws_bytes < poetx_linear_workspace_bytes(desc)) return POETX_ERR_WORKSPACE;
-  hipStream_t st = (hipStream_t)stream;
+                          hipStream_t st) {
   const int m = desc->d_in, n = desc->d_out, b = desc->block, dt = desc->dtype, k = desc->neumann_k;
   const i64 N = desc->n_tokens;
   const int dmax = m > n ? m : n;
@@ -322,22 +353,15 @@ int poetx_linear_bwd_skew(const poetx_linear_desc* desc, const void* X, const vo
       const float* dQ = mfma_cnp_bwd_chain(Qf, Tb, dG, nbt, b, k, chain, st);
       skew_project_launch(dQ, b, n, dtheta_P, accumulate != 0, st);
       skew_project_launch(dQ + nbP * bb, b, m, dtheta_R, accumulate != 0, st);
-      return launch_status();
+      return;
     }
-    uint16_t* Qb = (uint16_t*)(dG + nbt * bb);                // [nbt][b][b] bf16 (one float slot per element)
-    float* chain = dG + 2 * nbt * bb;                         // (k + 1) * nbt * b * b floats
     {
       StageTimer tm(POETX_STAGE_BLOCKGRAD, st);
       mfma_blockgrad(saved_B, dZ, n, N, perm_P, b, dG, bg_ws, st);            // dG_P = B' dZ'^T
       mfma_blockgrad(X, dA, m, N, perm_R, b, dG + nbP * bb, bg_ws, st);       // dG_R = X' dA'^T
     }
-    StageTimer tm(POETX_STAGE_CNP_BWD, st);
-    skew_materialize_launch(theta_P, b, nbP, nullptr, Qb, nullptr, st);
-    skew_materialize_launch(theta_R, b, nbR, nullptr, Qb + nbP * bb, nullptr, st);
-    const float* dQ = lds_cnp_bwd_chain(Qb, dG, nbt, k, chain, st);
-    skew_project_launch(dQ, b, n, dtheta_P, accumulate != 0, st);
-    skew_project_launch(dQ + nbP * bb, b, m, dtheta_R, accumulate != 0, st);
-    return launch_status();
+    cnp_bwd_both_on_chip(theta_R, theta_P, dG, m, n, b, k, dtheta_R, dtheta_P, accumulate, st);
+    return;
   }
   float* dG = (float*)ws;
   float* chain = dG + (size_t)ceil_div(dmax, b) * b * b;
@@ -360,6 +384,66 @@ int poetx_linear_bwd_skew(const poetx_linear_desc* desc, const void* X, const vo
       else fma_cnp_bwd(theta, dG, d, b, k, dtheta, accumulate != 0, chain, st);
     }
   }
+}
+
+int poetx_linear_bwd_skew(const poetx_linear_desc* desc, const void* X, const void* dZ, const void* saved_B,
+                          const void* dA, const int32_t* perm_R, const int32_t* perm_P, const float* theta_R,
+                          const float* theta_P, float* dtheta_R, float* dtheta_P, int32_t accumulate, void* ws,
+                          size_t ws_bytes, void* stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (!X || !dZ || !saved_B || !dA || !perm_R || !perm_P || !theta_R || !theta_P || !dtheta_R || !dtheta_P)
+    return POETX_ERR_INVALID_ARG;
+  if (!ws || ws_bytes < poetx_linear_workspace_bytes(desc)) return POETX_ERR_WORKSPACE;
+  bwd_skew_impl(desc, X, dZ, saved_B, dA, perm_R, perm_P, theta_R, theta_P, dtheta_R, dtheta_P, accumulate, ws,
+                (hipStream_t)stream);
+  return launch_status();
+}
+
+int poetx_linear_bwd(const poetx_linear_desc* desc, const void* X, const void* dZ, const void* saved_B, const void* W,
+                     const int32_t* perm_R, const int32_t* perm_P, const void* blocks_R, const void* blocks_P,
+                     const float* theta_R, const float* theta_P, void* dX, float* dtheta_R, float* dtheta_P,
+                     int32_t accumulate, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_desc(desc);
+  if (rc) return rc;
+  if (!X || !dZ || !saved_B || !W || !perm_R || !perm_P || !blocks_R || !blocks_P || !theta_R || !theta_P || !dX ||
+      !dtheta_R || !dtheta_P)
+    return POETX_ERR_INVALID_ARG;
+  if (!ws || ws_bytes < poetx_linear_workspace_bytes(desc)) return POETX_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  const int m = desc->d_in, n = desc->d_out, b = desc->block, dt = desc->dtype, k = desc->neumann_k;
+  const i64 N = desc->n_tokens;
+  void* dA = ws;                                                   // m x N, lives until the R side is done
+  char* rest = (char*)ws + align256((size_t)m * N * esize(dt));
+  const bool one_pass = desc->cnp_precision == POETX_CNP_BF16 && use_mfma(dt) && lds_cnp_supported(m, b) &&
+                        lds_cnp_supported(n, b) && mfma_apply_grad_supported(m, N, N, b) &&
+                        mfma_apply_grad_supported(n, N, N, b);
+  if (!one_pass) {   // the same values through the two halves
+    bwd_input_impl(desc, dZ, W, perm_R, perm_P, blocks_R, blocks_P, dX, dA, rest, st);
+    bwd_skew_impl(desc, X, dZ, saved_B, dA, perm_R, perm_P, theta_R, theta_P, dtheta_R, dtheta_P, accumulate, rest, st);
+    return launch_status();
+  }
+  // Each side's gradient is streamed once: dB = P dZ together with dG_P = B' dZ'^T, then
+  // dA = W^T dB, then dX = R dA together with dG_R = X' dA'^T (Sec. 3.5), then the series backward.
+  void* dB = rest;
+  char* after_dB = rest + align256((size_t)n * N * esize(dt));
+  const int nbP = n / b, nbR = m / b;
+  const size_t bb = (size_t)b * b;
+  float* dG = (float*)after_dB;                                    // both sides' block gradients, then chain scratch
+  size_t chain_floats = cnp_bwd_ws_floats(m > n ? m : n, b, k);
+  if (cnp_bwd_ws_floats_both(m, n, b, k) > chain_floats) chain_floats = cnp_bwd_ws_floats_both(m, n, b, k);
+  void* part = after_dB + align256(chain_floats * sizeof(float));
+  {
+    StageTimer tm(POETX_STAGE_APPLY_GRAD, st);
+    mfma_apply_grad(dZ, saved_B, dB, n, N, N, perm_P, blocks_P, 0, dG, part, st);
+  }
+  W = resolve_weight(desc, W, part, st);   // the P side's partials are reduced by now (stream order): same space
+  dense_dispatch(dt, 1, W, n, m, dB, dA, N, st);
+  {
+    StageTimer tm(POETX_STAGE_APPLY_GRAD, st);
+    mfma_apply_grad(dA, X, dX, m, N, N, perm_R, blocks_R, 0, dG + nbP * bb, part, st);
+  }
+  cnp_bwd_both_on_chip(theta_R, theta_P, dG, m, n, b, k, dtheta_R, dtheta_P, accumulate, st);
   return launch_status();
 }
 

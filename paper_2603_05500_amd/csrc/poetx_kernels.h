@@ -56,6 +56,13 @@ bool mfma_blockgrad_supported(int d, i64 N, int b);
 size_t mfma_blockgrad_workspace_bytes(int d, i64 N, int b);
 void mfma_blockgrad(const void* U, const void* V, int d, i64 N, const int32_t* perm, int b, float* dG,
                     void* ws, hipStream_t st);
+// One pass over the incoming gradient V (d x N) for one side (mfma_applygrad.hip, b = 256):
+// out = Psi^T Diag(op(G)) Psi V and dG[j] = U'_j V'_j^T (rows gathered by perm).  ws: the bytes the
+// query reports (partial block gradients of the token ranges).
+bool mfma_apply_grad_supported(int d, i64 N, i64 ld, int b);
+size_t mfma_apply_grad_workspace_bytes(int d, i64 N);
+void mfma_apply_grad(const void* V, const void* U, void* out, int d, i64 N, i64 ld, const int32_t* perm, const void* E,
+                     int transpose_G, float* dG, void* ws, hipStream_t st);
 bool mfma_cnp_supported(int d, int b);
 void mfma_cnp_build(const float* theta, int d, int b, int k, float* G_f32, void* E_bf16, float* ws,
                     hipStream_t st);

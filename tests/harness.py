@@ -99,8 +99,15 @@ def run_layer(data: dict, dtype_name: str, cnp_precision=None) -> dict:
     px.poetx_linear_fwd(desc, X, W, pi_R, pi_P, blk_R, blk_P, Z, B, ws)
     px.poetx_linear_bwd_input(desc, dZ, W, pi_R, pi_P, blk_R, blk_P, dX, dA, ws)
     px.poetx_linear_bwd_skew(desc, X, dZ, B, dA, pi_R, pi_P, th_R, th_P, dth_R, dth_P, False, ws)
+    # the whole backward pass in one call, on a workspace of its own poisoned with NaNs
+    ws1 = torch.full((ws.numel() // 4,), float("nan"), dtype=torch.float32, device="cuda").view(torch.uint8)
+    dX1 = torch.full_like(dX, float("nan"))
+    dth_R1 = torch.full_like(th_R, float("nan"))
+    dth_P1 = torch.full_like(th_P, float("nan"))
+    px.poetx_linear_bwd(desc, X, dZ, B, W, pi_R, pi_P, blk_R, blk_P, th_R, th_P, dX1, dth_R1, dth_P1, False, ws1)
     torch.cuda.synchronize()
     return {"G_R": G_R, "G_P": G_P, "Z": to_np(Z), "B": to_np(B), "dX": to_np(dX), "dA": to_np(dA),
             "dtheta_R": to_np(dth_R), "dtheta_P": to_np(dth_P),
+            "one_call": {"dX": to_np(dX1), "dtheta_R": to_np(dth_R1), "dtheta_P": to_np(dth_P1)},
             "dev": {"X": X, "dZ": dZ, "W": W, "pi_R": pi_R, "pi_P": pi_P, "blk_R": blk_R, "blk_P": blk_P,
                     "Z": Z, "B": B, "dX": dX, "dA": dA, "th_R": th_R, "th_P": th_P, "desc": desc, "ws": ws}}

@@ -62,7 +62,9 @@ def test_fullsize_sampled(lib, cfg_key, proj, step):
     B_ref = np.empty_like(f["Bp"])
     B_ref[pi_P, :] = f["Bp"]
     errs, rows, p999 = {}, {}, {}
-    for key, got, ref in (("Z", res["Z"][:, T], f["Z"]), ("B", res["B"][:, T], B_ref), ("dX", res["dX"][:, T], g["dX"])):
+    one = res["one_call"]   # poetx_linear_bwd on the same inputs
+    for key, got, ref in (("Z", res["Z"][:, T], f["Z"]), ("B", res["B"][:, T], B_ref), ("dX", res["dX"][:, T], g["dX"]),
+                          ("one-call dX", one["dX"][:, T], g["dX"])):
         errs[key], rows[key], p999[key] = rel_err(got, ref), row_rel_err(got, ref), p999_err(got, ref)
 
     # --- sampled blocks: packed-parameter gradients (reduction over all N tokens)
@@ -85,9 +87,11 @@ def test_fullsize_sampled(lib, cfg_key, proj, step):
             key = f"dtheta_{side}[{j}]"
             # one block is one "row" of the packed gradient: rel_err on it is the per-row metric
             errs[key], p999[key] = rel_err(got, ref), p999_err(got, ref)
+            errs["one-call " + key] = rel_err(one["dtheta_" + side][j], ref)
     fmt = lambda d: {key: float(f"{v:.3e}") for key, v in d.items()}
     print("max-normalised:", fmt(errs), flush=True)
     print("worst row:", fmt(rows), "p99.9 element-wise:", fmt(p999), flush=True)
     bad = {key: v for key, v in {**errs, **{"row " + k2: v for k2, v in rows.items()}}.items() if not v <= tol}
     assert not bad, f"over tolerance {tol}: {bad}"
     assert np.isfinite(res["dtheta_R"]).all() and np.isfinite(res["dtheta_P"]).all()
+    assert np.isfinite(one["dtheta_R"]).all() and np.isfinite(one["dtheta_P"]).all() and np.isfinite(one["dX"]).all()

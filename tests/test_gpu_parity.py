@@ -156,6 +156,9 @@ def check_layer(res, ref, pi_P, dtype):
     pairs = {"G_R-I": (res["G_R"] - eye, ref["G_R"] - eye), "G_P-I": (res["G_P"] - eye, ref["G_P"] - eye),
              "Z": (res["Z"], ref["Z"]), "B": (res["B"], B_ref), "dX": (res["dX"], ref["dX"]),
              "dtheta_R": (res["dtheta_R"], ref["dtheta_R"]), "dtheta_P": (res["dtheta_P"], ref["dtheta_P"])}
+    if "one_call" in res:   # poetx_linear_bwd: the same three outputs from the single backward call
+        for key in ("dX", "dtheta_R", "dtheta_P"):
+            pairs["one-call " + key] = (res["one_call"][key], ref[key])
     for key, (got, want) in pairs.items():
         errs[key] = rel_err(got, want)
         errs["row " + key] = row_rel_err(got, want)
