@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--variant", default="fast", choices=["fast", "mem", "xq"],
                     help="fast keeps B from the forward pass (the measured metric); mem recomputes it in backward; "
                          "xq is mem on an INT8 base weight that every dense product dequantises first")
+    ap.add_argument("--per-projection-series", action="store_true",
+                    help="build the blocks and run the series backward once per projection instead of once per "
+                         "layer step for all seven projections together")
     ap.add_argument("--two-call-backward", action="store_true",
                     help="run the backward pass as poetx_linear_bwd_input + poetx_linear_bwd_skew instead of the "
                          "single poetx_linear_bwd call")
@@ -225,6 +228,29 @@ def main():
     dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     N, b, k = cfg.n_tokens, cfg.block, cfg.neumann_k
     projs = make_inputs(cfg, torch)
+    # The series of a block does not depend on the projection it belongs to: when b divides every
+    # dimension, the packed parameters, blocks, block gradients and parameter gradients of all seven
+    # projections live end to end in layer-wide buffers, so that ONE poetx_cnp_build at the start of a
+    # step and ONE poetx_cnp_bwd at its end serve the whole layer (320 chains fill the GPU; the 8 to 72
+    # of one projection do not).
+    layer_series = (not args.per_projection_series and cfg.dtype == "bf16" and all(p["one_build"] for p in projs)
+                    and not args.two_call_backward)
+    if layer_series:
+        nbt = sum(p["theta_all"].shape[0] for p in projs)
+        theta_layer = torch.cat([p["theta_all"] for p in projs], 0).contiguous()
+        blk_layer = torch.empty((nbt, 2, b, b), device="cuda", dtype=torch.bfloat16)
+        dG_layer = torch.empty((nbt, b, b), device="cuda", dtype=torch.float32)
+        dtheta_layer = torch.empty_like(theta_layer)
+        lo = 0
+        for p in projs:
+            nR, nP = p["theta_R"].shape[0], p["theta_P"].shape[0]
+            p["theta_all"] = theta_layer[lo:lo + nR + nP]
+            p["theta_R"], p["theta_P"] = theta_layer[lo:lo + nR], theta_layer[lo + nR:lo + nR + nP]
+            p["blk_R"], p["blk_P"] = blk_layer[lo:lo + nR], blk_layer[lo + nR:lo + nR + nP]
+            p["dG_R"], p["dG_P"] = dG_layer[lo:lo + nR], dG_layer[lo + nR:lo + nR + nP]
+            p["dtheta_R"], p["dtheta_P"] = dtheta_layer[lo:lo + nR], dtheta_layer[lo + nR:lo + nR + nP]
+            lo += nR + nP
+        d_layer = nbt * b
     nmax = max(p["n"] for p in projs)
     mmax = max(p["m"] for p in projs)
     Z = torch.empty((nmax, N), device="cuda", dtype=dt)
@@ -234,6 +260,8 @@ def main():
     ws_bytes = cnp_bytes = 0
     for p in projs:
         flags = {"fast": 0, "mem": px.FLAG_RECOMPUTE_B, "xq": px.FLAG_RECOMPUTE_B | px.FLAG_W_INT8}[args.variant]
+        if layer_series:
+            flags |= px.FLAG_BLOCK_GRADS
         p["desc"] = px.make_desc(p["m"], p["n"], b, k, N, code, flags=flags)
         if args.variant == "xq":   # only the 8-bit weight stays resident
             wq = torch.zeros(px.poetx_weight_q8_bytes(p["n"], p["m"]), dtype=torch.uint8, device="cuda")
@@ -242,6 +270,8 @@ def main():
             p["W"] = wq
         ws_bytes = max(ws_bytes, px.poetx_linear_workspace_bytes(p["desc"]))
         cnp_bytes = max(cnp_bytes, px.poetx_cnp_workspace_bytes(p["m"] + p["n"], b))
+    if layer_series:
+        cnp_bytes = max(px.poetx_cnp_workspace_bytes(d_layer, b), px.poetx_cnp_bwd_workspace_bytes(d_layer, b, k))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     cws = torch.empty(cnp_bytes, dtype=torch.uint8, device="cuda")
     prec = px.CNP_BF16 if code == px.BF16 else px.CNP_FP32
@@ -249,11 +279,15 @@ def main():
     step_no = [0]
 
     def step():
+        if layer_series:
+            px.poetx_cnp_build(theta_layer, d_layer, b, k, prec, ws=cws, E_bf16=blk_layer)
         for p in projs:
             m, n = p["m"], p["n"]
             p["pi_R"] = p["pool_R"][step_no[0] % len(p["pool_R"])]
             p["pi_P"] = p["pool_P"][step_no[0] % len(p["pool_P"])]
-            if p["one_build"]:
+            if layer_series:
+                pass
+            elif p["one_build"]:
                 kw = {"E_bf16": p["blk_all"]} if code == px.BF16 else {"G_f32": p["blk_all"]}
                 px.poetx_cnp_build(p["theta_all"], m + n, b, k, prec, ws=cws, **kw)
             else:
@@ -272,8 +306,11 @@ def main():
                                          p["theta_R"], p["theta_P"], p["dtheta_R"], p["dtheta_P"], False, ws)
             else:   # the whole backward pass in one call: each side's gradient is streamed once
                 px.poetx_linear_bwd(p["desc"], p["X"], p["dZ"], B[:n], p["W"], p["pi_R"], p["pi_P"], p["blk_R"],
-                                    p["blk_P"], p["theta_R"], p["theta_P"], dX[:m], p["dtheta_R"], p["dtheta_P"],
-                                    False, ws)
+                                    p["blk_P"], p["theta_R"], p["theta_P"], dX[:m],
+                                    p["dG_R"] if layer_series else p["dtheta_R"],
+                                    p["dG_P"] if layer_series else p["dtheta_P"], False, ws)
+        if layer_series:
+            px.poetx_cnp_bwd(theta_layer, dG_layer, d_layer, b, k, prec, dtheta_layer, False, cws)
         step_no[0] += 1
 
     if args.copy_calibration:
@@ -330,7 +367,9 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: one decoder layer = 7 POET-X linears "
                                f"({', '.join(f'{p.name} {p.d_out}x{p.d_in}' for p in cfg.projections)}), "
-                               f"N={N} tokens, b={b}, k={k}, fwd + bwd_input + bwd_skew + cnp_build, {args.variant} variant"
+                               f"N={N} tokens, b={b}, k={k}, cnp_build + fwd + bwd (input and skew-parameter gradients), "
+                               f"{args.variant} variant"
+                               + (", blocks built and series backward run once per step for the whole layer" if layer_series else "")
                                + (", a fresh permutation pair per projection every step" if cfg.fresh_perms else ""),
                    "tokens_per_step": N, "block": b, "neumann_k": k},
         "mfma_peak_frac_layer": (dense_f + block_f + cnp_f) / (ms * 1e-3) / (PEAK_BF16_TFLOPS * 1e12),

@@ -106,6 +106,14 @@ typedef struct {
  * alone it is POETX_ERR_INVALID_ARG.  The flag enlarges the workspace by one n x m weight. */
 #define POETX_FLAG_W_INT8 2
 
+/* Deferred series backward: poetx_linear_bwd_skew and poetx_linear_bwd stop after the block
+ * gradients (Sec. 3.5: dG_P^j = B'_j dZ'_j^T, dG_R^j = X'_j dA'_j^T) and write them where they
+ * would have written the parameter gradients: dtheta_R / dtheta_P are then float [ceil(m/b)][b][b] /
+ * [ceil(n/b)][b][b] buffers (overwritten; `accumulate` is ignored).  poetx_cnp_bwd turns block
+ * gradients into parameter gradients for any batch of blocks, so one call can serve all
+ * projections of a layer -- the chains of a single projection leave most of the GPU idle. */
+#define POETX_FLAG_BLOCK_GRADS 4
+
 const char* poetx_status_string(int status);
 
 /* Library version (major * 100 + minor). */
@@ -160,6 +168,15 @@ int poetx_cnp_build(const float* theta, int32_t d, int32_t b, int32_t k, int32_t
 #define POETX_CNP_STATIC_MAX_ELEMS (1u << 22)   /* e.g. d = 16384 at b = 256, d = 8192 at b = 512 */
 int poetx_cnp_build_static(const float* theta, int32_t d, int32_t b, int32_t k, int32_t precision,
                            float* G_f32, void* E_bf16, void* stream);
+
+/* Backward of skew_symmetric + cayley_neumann (the Sec. 3.4 backward display, for any k), batched
+ * over blocks: dG [nb][b][b] float = dL/dG -> dtheta [nb][b(b-1)/2] float, overwritten when
+ * accumulate == 0 and added to otherwise; theta, d, b, k, precision as in poetx_cnp_build (the
+ * blocks may be those of several sides or projections laid end to end when b divides each of
+ * their dimensions).  ws: poetx_cnp_bwd_workspace_bytes(d, b, k) bytes. */
+size_t poetx_cnp_bwd_workspace_bytes(int32_t d, int32_t b, int32_t k);
+int poetx_cnp_bwd(const float* theta, const float* dG, int32_t d, int32_t b, int32_t k, int32_t precision,
+                  float* dtheta, int32_t accumulate, void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------
  * INT8 codes of a base weight (Sec. 3.6; scheme and buffer layout: see POETX_FLAG_W_INT8).

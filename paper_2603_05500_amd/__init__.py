@@ -19,10 +19,11 @@ F32, BF16 = 0, 1
 CNP_FP32, CNP_BF16 = 0, 1
 FLAG_RECOMPUTE_B = 1
 FLAG_W_INT8 = 2
+FLAG_BLOCK_GRADS = 4
 
 EXPORTS = (
     "poetx_status_string", "poetx_version", "poetx_debug_force_fma",
-    "poetx_cnp_workspace_bytes", "poetx_cnp_build", "poetx_cnp_build_static",
+    "poetx_cnp_workspace_bytes", "poetx_cnp_build", "poetx_cnp_build_static", "poetx_cnp_bwd_workspace_bytes", "poetx_cnp_bwd",
     "poetx_perm_blockdiag_apply_left", "poetx_perm_blockdiag_apply_right", "poetx_perm_validate",
     "poetx_linear_workspace_bytes", "poetx_linear_fwd", "poetx_linear_bwd_input", "poetx_linear_bwd_skew",
     "poetx_linear_recompute_b", "poetx_linear_bwd",
@@ -67,6 +68,11 @@ def load_library(path: str | None = None):
     lib.poetx_cnp_build.restype = c_int
     lib.poetx_cnp_build.argtypes = [c_void_p, c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p,
                                     c_void_p, c_size_t, c_void_p]
+    lib.poetx_cnp_bwd_workspace_bytes.restype = c_size_t
+    lib.poetx_cnp_bwd_workspace_bytes.argtypes = [c_int32, c_int32, c_int32]
+    lib.poetx_cnp_bwd.restype = c_int
+    lib.poetx_cnp_bwd.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_int32, c_int32, c_void_p, c_int32, c_void_p,
+                                  c_size_t, c_void_p]
     lib.poetx_cnp_build_static.restype = c_int
     lib.poetx_cnp_build_static.argtypes = [c_void_p, c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p]
     for name in ("poetx_perm_blockdiag_apply_left",):
@@ -163,6 +169,17 @@ def poetx_cnp_build(theta, d, b, k, precision, G_f32=None, E_bf16=None, ws=None)
     _check(lib.poetx_cnp_build(_ptr(theta), d, b, k, precision, _ptr(G_f32), _ptr(E_bf16), _ptr(ws),
                                ws.numel() * ws.element_size() if ws is not None else 0, _stream()),
            "poetx_cnp_build")
+
+
+def poetx_cnp_bwd_workspace_bytes(d: int, b: int, k: int) -> int:
+    return load_library().poetx_cnp_bwd_workspace_bytes(d, b, k)
+
+
+def poetx_cnp_bwd(theta, dG, d, b, k, precision, dtheta, accumulate, ws):
+    lib = load_library()
+    _check(lib.poetx_cnp_bwd(_ptr(theta), _ptr(dG), d, b, k, precision, _ptr(dtheta), int(bool(accumulate)), _ptr(ws),
+                             _ws_bytes(ws), _stream()),
+           "poetx_cnp_bwd")
 
 
 def poetx_cnp_build_static(theta, d, b, k, precision, G_f32=None, E_bf16=None):

@@ -51,7 +51,7 @@ int check_desc(const poetx_linear_desc* d) {
     return POETX_ERR_INVALID_ARG;
   if (!dtype_ok(d->dtype)) return POETX_ERR_INVALID_ARG;
   if (d->cnp_precision != POETX_CNP_FP32 && d->cnp_precision != POETX_CNP_BF16) return POETX_ERR_INVALID_ARG;
-  if ((d->flags & ~(POETX_FLAG_RECOMPUTE_B | POETX_FLAG_W_INT8)) != 0 || d->reserved != 0) return POETX_ERR_INVALID_ARG;
+  if ((d->flags & ~(POETX_FLAG_RECOMPUTE_B | POETX_FLAG_W_INT8 | POETX_FLAG_BLOCK_GRADS)) != 0 || d->reserved != 0) return POETX_ERR_INVALID_ARG;
   if ((d->flags & POETX_FLAG_W_INT8) && !(d->flags & POETX_FLAG_RECOMPUTE_B)) return POETX_ERR_INVALID_ARG;
   if (d->block > d->d_in || d->block > d->d_out) return POETX_ERR_BAD_SHAPE;
   if (d->n_tokens >= (1ll << 31) || (i64)d->n_tokens * (d->d_in > d->d_out ? d->d_in : d->d_out) >= (1ll << 40))
@@ -145,6 +145,26 @@ int poetx_cnp_build_static(const float* theta, int32_t d, int32_t b, int32_t k, 
   if (rc != POETX_OK) return rc;
   // every scratch element the kernels read was written earlier in the same call: nothing to clear
   return poetx_cnp_build(theta, d, b, k, precision, G_f32, E_bf16, ws, kStaticCnpBytes, stream);
+}
+
+size_t poetx_cnp_bwd_workspace_bytes(int32_t d, int32_t b, int32_t k) {
+  if (d <= 0 || b <= 0 || k < 1) return 0;
+  return align256((cnp_bwd_ws_floats(d, b, k) - (size_t)ceil_div(d, b) * b * b) * sizeof(float));   // without dG itself
+}
+
+int poetx_cnp_bwd(const float* theta, const float* dG, int32_t d, int32_t b, int32_t k, int32_t precision,
+                  float* dtheta, int32_t accumulate, void* ws, size_t ws_bytes, void* stream) {
+  if (!theta || !dG || !dtheta || d <= 0 || b <= 0 || k < 1) return POETX_ERR_INVALID_ARG;
+  if (precision != POETX_CNP_FP32 && precision != POETX_CNP_BF16) return POETX_ERR_INVALID_ARG;
+  if (b > d) return POETX_ERR_BAD_SHAPE;
+  if (!ws || ws_bytes < poetx_cnp_bwd_workspace_bytes(d, b, k)) return POETX_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  StageTimer tm(POETX_STAGE_CNP_BWD, st);
+  if (precision == POETX_CNP_BF16 && !g_force_fma.load() && mfma_cnp_supported(d, b))
+    mfma_cnp_bwd(theta, dG, d, b, k, dtheta, accumulate != 0, (float*)ws, st);
+  else
+    fma_cnp_bwd(theta, dG, d, b, k, dtheta, accumulate != 0, (float*)ws, st);
+  return launch_status();
 }
 
 size_t poetx_weight_q8_bytes(int32_t n, int32_t m) {
@@ -331,6 +351,9 @@ static void bwd_skew_impl(const poetx_linear_desc* desc, const void* X, const vo
   size_t chain_floats = cnp_bwd_ws_floats(dmax, b, k);
   if (cnp_bwd_ws_floats_both(m, n, b, k) > chain_floats) chain_floats = cnp_bwd_ws_floats_both(m, n, b, k);
   void* bg_ws = (char*)ws + align256(chain_floats * sizeof(float));
+  // POETX_FLAG_BLOCK_GRADS: the block gradients go to the caller (in place of dtheta) and the series
+  // backward is left to poetx_cnp_bwd
+  const bool defer = (desc->flags & POETX_FLAG_BLOCK_GRADS) != 0;
   if (desc->cnp_precision == POETX_CNP_BF16 && !g_force_fma.load() && use_mfma(dt) && mfma_cnp_supported(m, b) &&
       mfma_cnp_supported(n, b) && mfma_blockgrad_supported(m, N, b) && mfma_blockgrad_supported(n, N, b)) {
     // Both sides' blocks go through the series backward as one batch (P side first): the chains
@@ -338,6 +361,12 @@ static void bwd_skew_impl(const poetx_linear_desc* desc, const void* X, const vo
     const int nbP = n / b, nbR = m / b, nbt = nbP + nbR;
     const size_t bb = (size_t)b * b;
     float* dG = (float*)ws;                                   // [nbt][b][b]
+    if (defer) {
+      StageTimer tm(POETX_STAGE_BLOCKGRAD, st);
+      mfma_blockgrad(saved_B, dZ, n, N, perm_P, b, dtheta_P, bg_ws, st);
+      mfma_blockgrad(X, dA, m, N, perm_R, b, dtheta_R, bg_ws, st);
+      return;
+    }
     if (!lds_cnp_supported(m, b)) {                            // tiled kernels (b = 512)
       float* Qf = dG + nbt * bb;
       uint16_t* Tb = (uint16_t*)(Qf + nbt * bb);
@@ -373,12 +402,13 @@ static void bwd_skew_impl(const poetx_linear_desc* desc, const void* X, const vo
     const float* theta = side == 0 ? theta_P : theta_R;
     float* dtheta = side == 0 ? dtheta_P : dtheta_R;
     const bool fast_cnp = desc->cnp_precision == POETX_CNP_BF16 && !g_force_fma.load() && mfma_cnp_supported(d, b);
+    float* dGs = defer ? dtheta : dG;
     {
       StageTimer tm(POETX_STAGE_BLOCKGRAD, st);
-      if (use_mfma(dt) && mfma_blockgrad_supported(d, N, b)) mfma_blockgrad(U, V, d, N, perm, b, dG, bg_ws, st);
-      else fma_blockgrad(dt, U, V, d, N, perm, b, dG, st);
+      if (use_mfma(dt) && mfma_blockgrad_supported(d, N, b)) mfma_blockgrad(U, V, d, N, perm, b, dGs, bg_ws, st);
+      else fma_blockgrad(dt, U, V, d, N, perm, b, dGs, st);
     }
-    {
+    if (!defer) {
       StageTimer tm(POETX_STAGE_CNP_BWD, st);
       if (fast_cnp) mfma_cnp_bwd(theta, dG, d, b, k, dtheta, accumulate != 0, chain, st);
       else fma_cnp_bwd(theta, dG, d, b, k, dtheta, accumulate != 0, chain, st);
@@ -433,16 +463,20 @@ int poetx_linear_bwd(const poetx_linear_desc* desc, const void* X, const void* d
   size_t chain_floats = cnp_bwd_ws_floats(m > n ? m : n, b, k);
   if (cnp_bwd_ws_floats_both(m, n, b, k) > chain_floats) chain_floats = cnp_bwd_ws_floats_both(m, n, b, k);
   void* part = after_dB + align256(chain_floats * sizeof(float));
+  const bool defer = (desc->flags & POETX_FLAG_BLOCK_GRADS) != 0;   // block gradients to the caller, no series backward
+  float* dG_P = defer ? dtheta_P : dG;
+  float* dG_R = defer ? dtheta_R : dG + nbP * bb;
   {
     StageTimer tm(POETX_STAGE_APPLY_GRAD, st);
-    mfma_apply_grad(dZ, saved_B, dB, n, N, N, perm_P, blocks_P, 0, dG, part, st);
+    mfma_apply_grad(dZ, saved_B, dB, n, N, N, perm_P, blocks_P, 0, dG_P, part, st);
   }
   W = resolve_weight(desc, W, part, st);   // the P side's partials are reduced by now (stream order): same space
   dense_dispatch(dt, 1, W, n, m, dB, dA, N, st);
   {
     StageTimer tm(POETX_STAGE_APPLY_GRAD, st);
-    mfma_apply_grad(dA, X, dX, m, N, N, perm_R, blocks_R, 0, dG + nbP * bb, part, st);
+    mfma_apply_grad(dA, X, dX, m, N, N, perm_R, blocks_R, 0, dG_R, part, st);
   }
+  if (defer) return launch_status();
   cnp_bwd_both_on_chip(theta_R, theta_P, dG, m, n, b, k, dtheta_R, dtheta_P, accumulate, st);
   return launch_status();
 }

@@ -533,3 +533,66 @@ def test_bwd_skew_accumulates_on_the_batched_path(lib):
     torch.cuda.synchronize()
     assert np.array_equal(to_np(dR), (torch.from_numpy(res["dtheta_R"]).float() + 0.25).double().numpy())
     assert np.array_equal(to_np(dP), (torch.from_numpy(res["dtheta_P"]).float() - 0.5).double().numpy())
+
+
+# ------------------------------------------------------------------ deferred series backward
+@pytest.mark.parametrize("m,n,N,b,k,dtype", [(512, 768, 512, 256, 5, "bf16"), (1376, 512, 256, 64, 4, "bf16"),
+                                             (256, 256, 128, 32, 3, "f32"), (1024, 512, 256, 512, 3, "bf16")])
+def test_block_grads_and_cnp_bwd(lib, m, n, N, b, k, dtype):
+    """POETX_FLAG_BLOCK_GRADS: both backward entry points stop after the block gradients (checked against
+    the oracle's dG), and poetx_cnp_bwd finishes the job -- for both sides in one call when b divides
+    both dimensions, side by side otherwise."""
+    data = synth_layer(9900 + m + n + b, m, n, N, b, k, dtype, 0.01 if b < 256 else 0.005)
+    res = run_layer(data, dtype)
+    dev = res["dev"]
+    G_R = orc.cnp(orc.skew_from_packed(data["theta_R"], b, m), k)
+    G_P = orc.cnp(orc.skew_from_packed(data["theta_P"], b, n), k)
+    f = orc.linear_fwd(data["X"], data["W"], data["pi_R"], data["pi_P"], G_R, G_P)
+    g = orc.linear_bwd(data["dZ"], f, data["pi_R"], data["pi_P"], G_R, G_P)
+    ref = orc.linear_fwd_bwd_from_theta(data["X"], data["dZ"], data["W"], data["pi_R"], data["pi_P"],
+                                        data["theta_R"], data["theta_P"], b, k)
+    code = lib.F32 if dtype == "f32" else lib.BF16
+    desc = lib.make_desc(m, n, b, k, N, code, flags=lib.FLAG_BLOCK_GRADS)
+    nbR, nbP = orc.n_blocks(m, b), orc.n_blocks(n, b)
+    tol = TOL[dtype]
+    prec = lib.CNP_FP32 if dtype == "f32" else lib.CNP_BF16
+    for entry in ("bwd", "bwd_skew"):
+        dG = torch.full((nbR + nbP, b, b), float("nan"), dtype=torch.float32, device="cuda")
+        dG_R, dG_P = dG[:nbR], dG[nbR:]
+        if entry == "bwd":
+            dX = torch.empty_like(dev["dX"])
+            lib.poetx_linear_bwd(desc, dev["X"], dev["dZ"], dev["B"], dev["W"], dev["pi_R"], dev["pi_P"], dev["blk_R"],
+                                 dev["blk_P"], dev["th_R"], dev["th_P"], dX, dG_R, dG_P, False, dev["ws"])
+            torch.cuda.synchronize()
+            assert rel_err(to_np(dX), ref["dX"]) <= tol
+        else:
+            lib.poetx_linear_bwd_skew(desc, dev["X"], dev["dZ"], dev["B"], dev["dA"], dev["pi_R"], dev["pi_P"],
+                                      dev["th_R"], dev["th_P"], dG_R, dG_P, False, dev["ws"])
+            torch.cuda.synchronize()
+        # the oracle's blocks are exact for the tail's live part; dead rows / columns of a ragged tail hold
+        # whatever the padded reduction gives and are ignored by the series backward
+        for side, got, want, d in (("R", to_np(dG_R), g["dG_R"], m), ("P", to_np(dG_P), g["dG_P"], n)):
+            r = orc.tail_side(d, b)
+            got, want = got.copy(), want.copy()
+            got[-1, r:, :] = 0; got[-1, :, r:] = 0; want[-1, r:, :] = 0; want[-1, :, r:] = 0
+            assert rel_err(got, want) <= tol, (entry, side)
+            assert row_rel_err(got, want) <= tol, (entry, side)
+        # series backward of the two sides
+        if m % b == 0 and n % b == 0:   # one call for all blocks
+            th = torch.cat([dev["th_R"], dev["th_P"]], 0).contiguous()
+            dth = torch.full_like(th, float("nan"))
+            ws = ws_tensor(lib.poetx_cnp_bwd_workspace_bytes(m + n, b, k))
+            lib.poetx_cnp_bwd(th, dG, m + n, b, k, prec, dth, False, ws)
+            torch.cuda.synchronize()
+            got_R, got_P = to_np(dth[:nbR]), to_np(dth[nbR:])
+        else:
+            outs = []
+            for th, dGs, d in ((dev["th_R"], dG_R, m), (dev["th_P"], dG_P, n)):
+                dth = torch.full_like(th, float("nan"))
+                ws = ws_tensor(lib.poetx_cnp_bwd_workspace_bytes(d, b, k))
+                lib.poetx_cnp_bwd(th, dGs.contiguous(), d, b, k, prec, dth, False, ws)
+                torch.cuda.synchronize()
+                outs.append(to_np(dth))
+            got_R, got_P = outs
+        assert rel_err(got_R, ref["dtheta_R"]) <= tol and rel_err(got_P, ref["dtheta_P"]) <= tol, entry
+        assert row_rel_err(got_R, ref["dtheta_R"]) <= tol and row_rel_err(got_P, ref["dtheta_P"]) <= tol, entry
