@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--variant", default="fast", choices=["fast", "mem", "xq"],
                     help="fast keeps B from the forward pass (the measured metric); mem recomputes it in backward; "
                          "xq is mem on an INT8 base weight that every dense product dequantises first")
+    ap.add_argument("--layout", default="feature", choices=["feature", "token"],
+                    help="feature: X, Z, dZ, dX are [d][N] (native, the measured metric); token: [N][d], re-laid by "
+                         "the library on the way in and out")
     ap.add_argument("--per-projection-series", action="store_true",
                     help="build the blocks and run the series backward once per projection instead of once per "
                          "layer step for all seven projections together")
@@ -262,7 +265,12 @@ def main():
         flags = {"fast": 0, "mem": px.FLAG_RECOMPUTE_B, "xq": px.FLAG_RECOMPUTE_B | px.FLAG_W_INT8}[args.variant]
         if layer_series:
             flags |= px.FLAG_BLOCK_GRADS
-        p["desc"] = px.make_desc(p["m"], p["n"], b, k, N, code, flags=flags)
+        p["desc"] = px.make_desc(p["m"], p["n"], b, k, N, code, flags=flags,
+                                 layout=px.TOKEN_MAJOR if args.layout == "token" else px.FEATURE_MAJOR)
+        if args.layout == "token":
+            p["X"], p["dZ"] = p["X"].t().contiguous(), p["dZ"].t().contiguous()
+            p["Z_tm"] = torch.empty((N, p["n"]), device="cuda", dtype=dt)
+            p["dX_tm"] = torch.empty((N, p["m"]), device="cuda", dtype=dt)
         if args.variant == "xq":   # only the 8-bit weight stays resident
             wq = torch.zeros(px.poetx_weight_q8_bytes(p["n"], p["m"]), dtype=torch.uint8, device="cuda")
             px.poetx_weight_quantize_q8(p["W"], wq)
@@ -295,18 +303,20 @@ def main():
                 px.poetx_cnp_build(p["theta_R"], m, b, k, prec, ws=cws, **kw)
                 kw = {"E_bf16": p["blk_P"]} if code == px.BF16 else {"G_f32": p["blk_P"]}
                 px.poetx_cnp_build(p["theta_P"], n, b, k, prec, ws=cws, **kw)
+            Zp = p["Z_tm"] if args.layout == "token" else Z[:n]
+            dXp = p["dX_tm"] if args.layout == "token" else dX[:m]
             px.poetx_linear_fwd(p["desc"], p["X"], p["W"], p["pi_R"], p["pi_P"], p["blk_R"], p["blk_P"],
-                                Z[:n], None if args.variant != "fast" else B[:n], ws)
+                                Zp, None if args.variant != "fast" else B[:n], ws)
             if args.variant != "fast":
                 px.poetx_linear_recompute_b(p["desc"], p["X"], p["W"], p["pi_R"], p["blk_R"], B[:n], ws)
             if args.two_call_backward:
                 px.poetx_linear_bwd_input(p["desc"], p["dZ"], p["W"], p["pi_R"], p["pi_P"], p["blk_R"], p["blk_P"],
-                                          dX[:m], dA[:m], ws)
+                                          dXp, dA[:m], ws)
                 px.poetx_linear_bwd_skew(p["desc"], p["X"], p["dZ"], B[:n], dA[:m], p["pi_R"], p["pi_P"],
                                          p["theta_R"], p["theta_P"], p["dtheta_R"], p["dtheta_P"], False, ws)
             else:   # the whole backward pass in one call: each side's gradient is streamed once
                 px.poetx_linear_bwd(p["desc"], p["X"], p["dZ"], B[:n], p["W"], p["pi_R"], p["pi_P"], p["blk_R"],
-                                    p["blk_P"], p["theta_R"], p["theta_P"], dX[:m],
+                                    p["blk_P"], p["theta_R"], p["theta_P"], dXp,
                                     p["dG_R"] if layer_series else p["dtheta_R"],
                                     p["dG_P"] if layer_series else p["dtheta_P"], False, ws)
         if layer_series:
@@ -368,7 +378,7 @@ def main():
         "config": {"workload": f"{cfg.name}: one decoder layer = 7 POET-X linears "
                                f"({', '.join(f'{p.name} {p.d_out}x{p.d_in}' for p in cfg.projections)}), "
                                f"N={N} tokens, b={b}, k={k}, cnp_build + fwd + bwd (input and skew-parameter gradients), "
-                               f"{args.variant} variant"
+                               f"{args.variant} variant, {args.layout}-major activations"
                                + (", blocks built and series backward run once per step for the whole layer" if layer_series else "")
                                + (", a fresh permutation pair per projection every step" if cfg.fresh_perms else ""),
                    "tokens_per_step": N, "block": b, "neumann_k": k},

@@ -67,6 +67,15 @@ typedef enum {
 
 typedef enum { POETX_F32 = 0, POETX_BF16 = 1 } poetx_dtype;
 
+/* Layout of the activations a caller hands to the poetx_linear_* calls (X, Z, dZ, dX).
+ * FEATURE_MAJOR ([d][N], the library's native layout: the feature permutation of Eq. 5 is then a
+ * gather of whole rows, fused into the block kernels at no cost).  TOKEN_MAJOR ([N][d], what a
+ * framework usually holds): every such tensor is re-laid by one transposing pass through LDS on
+ * its way in or out (feature-major copies live in the workspace, which grows accordingly); all
+ * values are bit for bit those of the feature-major call.  saved_B, dA and the block gradients keep
+ * their layouts in both modes. */
+typedef enum { POETX_FEATURE_MAJOR = 0, POETX_TOKEN_MAJOR = 1 } poetx_layout;
+
 /* How the block products of the Cayley-Neumann chain are multiplied.
  * FP32: plain fp32 arithmetic.  BF16X1: operands rounded to bf16, fp32
  * accumulation on the matrix cores (meets the bf16 tolerance, not the fp32 one). */
@@ -82,7 +91,7 @@ typedef struct {
   int32_t dtype;       /* poetx_dtype of X, W, Z, saved B, gradients, blocks   */
   int32_t cnp_precision; /* poetx_cnp_precision used by poetx_linear_bwd_skew  */
   int32_t flags;       /* POETX_FLAG_* bits                                    */
-  int32_t reserved;    /* must be 0                                            */
+  int32_t layout;      /* poetx_layout of X, Z, dZ, dX (0 = feature major)     */
 } poetx_linear_desc;
 
 /* Memory-saving variant (Sec. 3.5, POET-X_mem): the forward pass keeps no activation
@@ -138,7 +147,8 @@ typedef enum {
   POETX_STAGE_BLOCKGRAD = 3,  /* per-block token reduction dG                    */
   POETX_STAGE_CNP_BWD = 4,    /* series backward + packed projection             */
   POETX_STAGE_APPLY_GRAD = 5, /* poetx_linear_bwd: structured product and block gradient of a side in one pass */
-  POETX_STAGE_COUNT = 6
+  POETX_STAGE_LAYOUT = 6,     /* token-major <-> feature-major passes            */
+  POETX_STAGE_COUNT = 7
 } poetx_stage;
 int poetx_profile_begin(int32_t max_records);
 int poetx_profile_end(double* ms_by_stage, int64_t* launches_by_stage);

@@ -20,6 +20,7 @@ CNP_FP32, CNP_BF16 = 0, 1
 FLAG_RECOMPUTE_B = 1
 FLAG_W_INT8 = 2
 FLAG_BLOCK_GRADS = 4
+FEATURE_MAJOR, TOKEN_MAJOR = 0, 1
 
 EXPORTS = (
     "poetx_status_string", "poetx_version", "poetx_debug_force_fma",
@@ -30,13 +31,13 @@ EXPORTS = (
     "poetx_weight_q8_bytes", "poetx_weight_quantize_q8", "poetx_weight_dequantize_q8",
     "poetx_profile_begin", "poetx_profile_end",
 )
-STAGES = ("cnp_fwd", "apply", "dense", "blockgrad", "cnp_bwd", "apply_grad")
+STAGES = ("cnp_fwd", "apply", "dense", "blockgrad", "cnp_bwd", "apply_grad", "layout")
 
 
 class LinearDesc(Structure):
     _fields_ = [("d_in", c_int32), ("d_out", c_int32), ("block", c_int32), ("neumann_k", c_int32),
                 ("n_tokens", c_int64), ("dtype", c_int32), ("cnp_precision", c_int32),
-                ("flags", c_int32), ("reserved", c_int32)]
+                ("flags", c_int32), ("layout", c_int32)]
 
 
 class PoetxError(RuntimeError):
@@ -146,10 +147,11 @@ def dtype_code(t) -> int:
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 
-def make_desc(d_in, d_out, block, neumann_k, n_tokens, dtype, cnp_precision=None, flags=0) -> LinearDesc:
+def make_desc(d_in, d_out, block, neumann_k, n_tokens, dtype, cnp_precision=None, flags=0,
+              layout=FEATURE_MAJOR) -> LinearDesc:
     if cnp_precision is None:
         cnp_precision = CNP_FP32 if dtype == F32 else CNP_BF16
-    return LinearDesc(d_in, d_out, block, neumann_k, n_tokens, dtype, cnp_precision, flags, 0)
+    return LinearDesc(d_in, d_out, block, neumann_k, n_tokens, dtype, cnp_precision, flags, layout)
 
 
 def poetx_debug_force_fma(on: bool):

@@ -51,7 +51,8 @@ int check_desc(const poetx_linear_desc* d) {
     return POETX_ERR_INVALID_ARG;
   if (!dtype_ok(d->dtype)) return POETX_ERR_INVALID_ARG;
   if (d->cnp_precision != POETX_CNP_FP32 && d->cnp_precision != POETX_CNP_BF16) return POETX_ERR_INVALID_ARG;
-  if ((d->flags & ~(POETX_FLAG_RECOMPUTE_B | POETX_FLAG_W_INT8 | POETX_FLAG_BLOCK_GRADS)) != 0 || d->reserved != 0) return POETX_ERR_INVALID_ARG;
+  if ((d->flags & ~(POETX_FLAG_RECOMPUTE_B | POETX_FLAG_W_INT8 | POETX_FLAG_BLOCK_GRADS)) != 0 || (d->layout != POETX_FEATURE_MAJOR && d->layout != POETX_TOKEN_MAJOR))
+    return POETX_ERR_INVALID_ARG;
   if ((d->flags & POETX_FLAG_W_INT8) && !(d->flags & POETX_FLAG_RECOMPUTE_B)) return POETX_ERR_INVALID_ARG;
   if (d->block > d->d_in || d->block > d->d_out) return POETX_ERR_BAD_SHAPE;
   if (d->n_tokens >= (1ll << 31) || (i64)d->n_tokens * (d->d_in > d->d_out ? d->d_in : d->d_out) >= (1ll << 40))
@@ -227,8 +228,59 @@ static const void* resolve_weight(const poetx_linear_desc* desc, const void* W, 
   return scratch;
 }
 
+// Token-major callers: feature-major copies of the call's activations (at most X, dZ / Z and dX)
+// live behind the regular workspace.
+static size_t layout_staging_bytes(const poetx_linear_desc* d) {
+  if (d->layout != POETX_TOKEN_MAJOR) return 0;
+  const size_t es = esize(d->dtype), N = (size_t)d->n_tokens;
+  return 2 * align256((size_t)d->d_in * N * es) + align256((size_t)d->d_out * N * es);
+}
+static size_t core_workspace_bytes(const poetx_linear_desc* desc);
+
 size_t poetx_linear_workspace_bytes(const poetx_linear_desc* desc) {
   if (check_desc(desc) != POETX_OK) return 0;
+  return core_workspace_bytes(desc) + layout_staging_bytes(desc);
+}
+
+// Feature-major <-> token-major copies around a call.  in(): the feature-major copy of a
+// token-major input (or the pointer itself); out(): where the call should write a feature-major
+// output; finish(): transposes the registered outputs into the caller's token-major buffers.
+class LayoutStaging {
+ public:
+  LayoutStaging(const poetx_linear_desc* d, void* ws, hipStream_t st)
+      : on_(d->layout == POETX_TOKEN_MAJOR), dt_(d->dtype), N_(d->n_tokens), st_(st),
+        next_((char*)ws + core_workspace_bytes(d)), n_out_(0) {}
+  const void* in(const void* p, int rows) {
+    if (!on_ || !p) return p;
+    void* t = take(rows);
+    StageTimer tm(POETX_STAGE_LAYOUT, st_);
+    transpose_launch(dt_, p, t, N_, rows, st_);        // [N][rows] -> [rows][N]
+    return t;
+  }
+  void* out(void* p, int rows) {
+    if (!on_ || !p) return p;
+    void* t = take(rows);
+    outs_[n_out_].user = p; outs_[n_out_].tmp = t; outs_[n_out_].rows = rows; ++n_out_;
+    return t;
+  }
+  void finish() {
+    for (int i = 0; i < n_out_; ++i) {
+      StageTimer tm(POETX_STAGE_LAYOUT, st_);
+      transpose_launch(dt_, outs_[i].tmp, outs_[i].user, outs_[i].rows, N_, st_);   // [rows][N] -> [N][rows]
+    }
+  }
+ private:
+  void* take(int rows) {
+    void* t = next_;
+    next_ += align256((size_t)rows * N_ * esize(dt_));
+    return t;
+  }
+  bool on_; int dt_; i64 N_; hipStream_t st_; char* next_;
+  struct { void* user; void* tmp; int rows; } outs_[2];
+  int n_out_;
+};
+
+static size_t core_workspace_bytes(const poetx_linear_desc* desc) {
   size_t es = esize(desc->dtype);
   size_t N = (size_t)desc->n_tokens;
   size_t fwd = align256((size_t)desc->d_in * N * es);   // A = R^T X
@@ -273,6 +325,9 @@ int poetx_linear_fwd(const poetx_linear_desc* desc, const void* X, const void* W
   hipStream_t st = (hipStream_t)stream;
   const int m = desc->d_in, n = desc->d_out, b = desc->block, dt = desc->dtype;
   const i64 N = desc->n_tokens;
+  LayoutStaging lay(desc, ws, st);
+  X = lay.in(X, m);
+  Z = lay.out(Z, n);
   void* A = ws;
   char* after = (char*)ws + align256((size_t)m * N * esize(dt));
   if (!saved_B) {  // memory-saving variant: scratch only
@@ -283,6 +338,7 @@ int poetx_linear_fwd(const poetx_linear_desc* desc, const void* X, const void* W
   apply_left_dispatch(dt, X, A, m, N, N, perm_R, blocks_R, b, 1, st);        // mm1: A = R^T X
   dense_dispatch(dt, 0, W, n, m, A, saved_B, N, st);                        // mm2: B = W A
   apply_left_dispatch(dt, saved_B, Z, n, N, N, perm_P, blocks_P, b, 1, st);  // mm3: Z = P^T B
+  lay.finish();
   return launch_status();
 }
 
@@ -295,6 +351,8 @@ int poetx_linear_recompute_b(const poetx_linear_desc* desc, const void* X, const
   hipStream_t st = (hipStream_t)stream;
   const int m = desc->d_in, n = desc->d_out, b = desc->block, dt = desc->dtype;
   const i64 N = desc->n_tokens;
+  LayoutStaging lay(desc, ws, st);
+  X = lay.in(X, m);
   W = resolve_weight(desc, W, (char*)ws + align256((size_t)m * N * esize(dt)), st);
   apply_left_dispatch(dt, X, ws, m, N, N, perm_R, blocks_R, b, 1, st);  // A = R^T X
   dense_dispatch(dt, 0, W, n, m, ws, B_out, N, st);                    // B = W A
@@ -321,7 +379,11 @@ int poetx_linear_bwd_input(const poetx_linear_desc* desc, const void* dZ, const 
   if (rc) return rc;
   if (!dZ || !W || !perm_R || !perm_P || !blocks_R || !blocks_P || !dX || !dA) return POETX_ERR_INVALID_ARG;
   if (!ws || ws_bytes < poetx_linear_workspace_bytes(desc)) return POETX_ERR_WORKSPACE;
+  LayoutStaging lay(desc, ws, (hipStream_t)stream);
+  dZ = lay.in(dZ, desc->d_out);
+  dX = lay.out(dX, desc->d_in);
   bwd_input_impl(desc, dZ, W, perm_R, perm_P, blocks_R, blocks_P, dX, dA, ws, (hipStream_t)stream);
+  lay.finish();
   return launch_status();
 }
 
@@ -425,6 +487,9 @@ int poetx_linear_bwd_skew(const poetx_linear_desc* desc, const void* X, const vo
   if (!X || !dZ || !saved_B || !dA || !perm_R || !perm_P || !theta_R || !theta_P || !dtheta_R || !dtheta_P)
     return POETX_ERR_INVALID_ARG;
   if (!ws || ws_bytes < poetx_linear_workspace_bytes(desc)) return POETX_ERR_WORKSPACE;
+  LayoutStaging lay(desc, ws, (hipStream_t)stream);
+  X = lay.in(X, desc->d_in);
+  dZ = lay.in(dZ, desc->d_out);
   bwd_skew_impl(desc, X, dZ, saved_B, dA, perm_R, perm_P, theta_R, theta_P, dtheta_R, dtheta_P, accumulate, ws,
                 (hipStream_t)stream);
   return launch_status();
@@ -443,6 +508,10 @@ int poetx_linear_bwd(const poetx_linear_desc* desc, const void* X, const void* d
   hipStream_t st = (hipStream_t)stream;
   const int m = desc->d_in, n = desc->d_out, b = desc->block, dt = desc->dtype, k = desc->neumann_k;
   const i64 N = desc->n_tokens;
+  LayoutStaging lay(desc, ws, st);
+  X = lay.in(X, m);
+  dZ = lay.in(dZ, n);
+  dX = lay.out(dX, m);
   void* dA = ws;                                                   // m x N, lives until the R side is done
   char* rest = (char*)ws + align256((size_t)m * N * esize(dt));
   const bool one_pass = desc->cnp_precision == POETX_CNP_BF16 && use_mfma(dt) && lds_cnp_supported(m, b) &&
@@ -451,13 +520,14 @@ int poetx_linear_bwd(const poetx_linear_desc* desc, const void* X, const void* d
   if (!one_pass) {   // the same values through the two halves
     bwd_input_impl(desc, dZ, W, perm_R, perm_P, blocks_R, blocks_P, dX, dA, rest, st);
     bwd_skew_impl(desc, X, dZ, saved_B, dA, perm_R, perm_P, theta_R, theta_P, dtheta_R, dtheta_P, accumulate, rest, st);
+    lay.finish();
     return launch_status();
   }
   // Each side's gradient is streamed once: dB = P dZ together with dG_P = B' dZ'^T, then
   // dA = W^T dB, then dX = R dA together with dG_R = X' dA'^T (Sec. 3.5), then the series backward.
   void* dB = rest;
   char* after_dB = rest + align256((size_t)n * N * esize(dt));
-  const int nbP = n / b, nbR = m / b;
+  const int nbP = n / b;
   const size_t bb = (size_t)b * b;
   float* dG = (float*)after_dB;                                    // both sides' block gradients, then chain scratch
   size_t chain_floats = cnp_bwd_ws_floats(m > n ? m : n, b, k);
@@ -476,6 +546,7 @@ int poetx_linear_bwd(const poetx_linear_desc* desc, const void* X, const void* d
     StageTimer tm(POETX_STAGE_APPLY_GRAD, st);
     mfma_apply_grad(dA, X, dX, m, N, N, perm_R, blocks_R, 0, dG_R, part, st);
   }
+  lay.finish();
   if (defer) return launch_status();
   cnp_bwd_both_on_chip(theta_R, theta_P, dG, m, n, b, k, dtheta_R, dtheta_P, accumulate, st);
   return launch_status();

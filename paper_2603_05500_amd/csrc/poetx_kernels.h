@@ -43,6 +43,9 @@ size_t weight_q8_scale_offset(int n, int m);
 void weight_quantize_q8_launch(int dtype, const void* W, int n, int m, void* Wq, hipStream_t st);
 void weight_dequantize_q8_launch(const void* Wq, int n, int m, int dtype, void* W_out, hipStream_t st);
 
+// out (C x R) = in (R x C)^T, both row major and dense (layout.hip)
+void transpose_launch(int dtype, const void* in, void* out, i64 R, i64 C, hipStream_t st);
+
 void perm_validate_launch(const int32_t* perm, int d, int32_t* scratch, hipStream_t st);
 
 // ---- matrix-core path for bf16 (mfma_*.hip) -------------------------------------------

@@ -596,3 +596,57 @@ def test_block_grads_and_cnp_bwd(lib, m, n, N, b, k, dtype):
             got_R, got_P = outs
         assert rel_err(got_R, ref["dtheta_R"]) <= tol and rel_err(got_P, ref["dtheta_P"]) <= tol, entry
         assert row_rel_err(got_R, ref["dtheta_R"]) <= tol and row_rel_err(got_P, ref["dtheta_P"]) <= tol, entry
+
+
+# ------------------------------------------------------------------ token-major activations
+@pytest.mark.parametrize("m,n,N,b,k,dtype", [(256, 256, 512, 32, 4, "f32"), (512, 1376, 1000, 64, 4, "bf16"),
+                                             (768, 512, 1280, 256, 5, "bf16"), (96, 40, 77, 8, 2, "f32")])
+def test_token_major_layout(lib, m, n, N, b, k, dtype):
+    """layout = POETX_TOKEN_MAJOR: X, Z, dZ, dX are [N][d].  The re-laying passes are exact, so every
+    output must be the transposed feature-major output bit for bit (which run_layer has already
+    produced and which is checked against the oracle here as well), through both backward routes."""
+    data = synth_layer(9950 + m + n + N, m, n, N, b, k, dtype, 0.01 if b < 256 else 0.005)
+    ref = orc.linear_fwd_bwd_from_theta(data["X"], data["dZ"], data["W"], data["pi_R"], data["pi_P"],
+                                        data["theta_R"], data["theta_P"], b, k)
+    res = run_layer(data, dtype)
+    check_layer(res, ref, data["pi_P"], dtype)
+    dev = res["dev"]
+    code = lib.F32 if dtype == "f32" else lib.BF16
+    desc = lib.make_desc(m, n, b, k, N, code, layout=lib.TOKEN_MAJOR)
+    fm = lib.make_desc(m, n, b, k, N, code)
+    es = 4 if dtype == "f32" else 2
+    assert lib.poetx_linear_workspace_bytes(desc) >= lib.poetx_linear_workspace_bytes(fm) + (2 * m + n) * N * es
+    ws = ws_tensor(lib.poetx_linear_workspace_bytes(desc))
+    Xt, dZt = dev["X"].t().contiguous(), dev["dZ"].t().contiguous()          # [N][m], [N][n]
+    Zt = torch.full((N, n), float("nan"), dtype=Xt.dtype, device="cuda")
+    B = torch.empty_like(dev["B"])
+    lib.poetx_linear_fwd(desc, Xt, dev["W"], dev["pi_R"], dev["pi_P"], dev["blk_R"], dev["blk_P"], Zt, B, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(Zt, dev["Z"].t()) and torch.equal(B, dev["B"])
+    assert rel_err(to_np(Zt).T, ref["Z"]) <= TOL[dtype]
+    # backward, two calls
+    dXt = torch.full((N, m), float("nan"), dtype=Xt.dtype, device="cuda")
+    dA = torch.empty_like(dev["dA"])
+    dR, dP = torch.full_like(dev["th_R"], float("nan")), torch.full_like(dev["th_P"], float("nan"))
+    lib.poetx_linear_bwd_input(desc, dZt, dev["W"], dev["pi_R"], dev["pi_P"], dev["blk_R"], dev["blk_P"], dXt, dA, ws)
+    lib.poetx_linear_bwd_skew(desc, Xt, dZt, B, dA, dev["pi_R"], dev["pi_P"], dev["th_R"], dev["th_P"], dR, dP, False, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dXt, dev["dX"].t()) and torch.equal(dA, dev["dA"])
+    assert np.array_equal(to_np(dR), res["dtheta_R"]) and np.array_equal(to_np(dP), res["dtheta_P"])
+    # backward, one call
+    dXt1 = torch.full((N, m), float("nan"), dtype=Xt.dtype, device="cuda")
+    dR1, dP1 = torch.full_like(dev["th_R"], float("nan")), torch.full_like(dev["th_P"], float("nan"))
+    lib.poetx_linear_bwd(desc, Xt, dZt, B, dev["W"], dev["pi_R"], dev["pi_P"], dev["blk_R"], dev["blk_P"],
+                         dev["th_R"], dev["th_P"], dXt1, dR1, dP1, False, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(dXt1).T, res["one_call"]["dX"])
+    assert np.array_equal(to_np(dR1), res["one_call"]["dtheta_R"]) and np.array_equal(to_np(dP1), res["one_call"]["dtheta_P"])
+    # memory-saving variant: recompute B from the token-major X
+    mem = lib.make_desc(m, n, b, k, N, code, flags=lib.FLAG_RECOMPUTE_B, layout=lib.TOKEN_MAJOR)
+    wsm = ws_tensor(lib.poetx_linear_workspace_bytes(mem))
+    B2 = torch.full_like(B, float("nan"))
+    lib.poetx_linear_recompute_b(mem, Xt, dev["W"], dev["pi_R"], dev["blk_R"], B2, wsm)
+    torch.cuda.synchronize()
+    assert torch.equal(B2, dev["B"])
+    # a layout code that does not exist is refused on the host
+    assert lib.poetx_linear_workspace_bytes(lib.make_desc(m, n, b, k, N, code, layout=2)) == 0
