@@ -108,11 +108,15 @@ typedef struct {
  *   W[i][k] ~ scale_i * q[i][k].
  * A quantised weight buffer is int8 q[n][m] row major followed, at byte offset
  * (n*m rounded up to 256), by float scale[n]; poetx_weight_q8_bytes gives its size.
- * With this flag the W argument of poetx_linear_fwd, poetx_linear_recompute_b and
- * poetx_linear_bwd_input is such a buffer: each call dequantises it into the workspace in the
- * layer's dtype right before its dense product and keeps nothing.  As in the paper the flag
- * is only valid together with POETX_FLAG_RECOMPUTE_B (the variant that keeps no activation);
- * alone it is POETX_ERR_INVALID_ARG.  The flag enlarges the workspace by one n x m weight. */
+ * With this flag the W argument of poetx_linear_fwd, poetx_linear_recompute_b,
+ * poetx_linear_bwd_input and poetx_linear_bwd is such a buffer.  For bf16 layers whose dimensions
+ * are multiples of 256 the dense products read the codes themselves: code tiles and row scales
+ * stream into LDS and are converted to bf16(scale * q) there, two stages ahead of the
+ * multiplication, so no high-precision weight is ever written to memory and the workspace is that of
+ * the plain memory-saving variant.  Other shapes and fp32 layers dequantise into the workspace
+ * (one n x m weight more) right before each dense product; the values are the same bit for bit.
+ * As in the paper the flag is only valid together with POETX_FLAG_RECOMPUTE_B (the variant that
+ * keeps no activation); alone it is POETX_ERR_INVALID_ARG. */
 #define POETX_FLAG_W_INT8 2
 
 /* Deferred series backward: poetx_linear_bwd_skew and poetx_linear_bwd stop after the block
@@ -148,7 +152,8 @@ typedef enum {
   POETX_STAGE_CNP_BWD = 4,    /* series backward + packed projection             */
   POETX_STAGE_APPLY_GRAD = 5, /* poetx_linear_bwd: structured product and block gradient of a side in one pass */
   POETX_STAGE_LAYOUT = 6,     /* token-major <-> feature-major passes            */
-  POETX_STAGE_COUNT = 7
+  POETX_STAGE_DEQUANT = 7,    /* INT8 weight dequantised into the workspace (shapes the fused kernel does not cover) */
+  POETX_STAGE_COUNT = 8
 } poetx_stage;
 int poetx_profile_begin(int32_t max_records);
 int poetx_profile_end(double* ms_by_stage, int64_t* launches_by_stage);

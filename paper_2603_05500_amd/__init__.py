@@ -31,7 +31,7 @@ EXPORTS = (
     "poetx_weight_q8_bytes", "poetx_weight_quantize_q8", "poetx_weight_dequantize_q8",
     "poetx_profile_begin", "poetx_profile_end",
 )
-STAGES = ("cnp_fwd", "apply", "dense", "blockgrad", "cnp_bwd", "apply_grad", "layout")
+STAGES = ("cnp_fwd", "apply", "dense", "blockgrad", "cnp_bwd", "apply_grad", "layout", "dequant")
 
 
 class LinearDesc(Structure):

@@ -81,11 +81,19 @@ void apply_left_dispatch(int dtype, const void* V, void* out, int d, i64 cols, i
     fma_apply_left(dtype, V, out, d, cols, ld, perm, blocks, b, trans, st);
 }
 
+// w_q8: W is a quantised weight buffer that the product dequantises itself (see weight_in_kernel)
 void dense_dispatch(int dtype, int trans_w, const void* W, int n, int m, const void* act, void* out, i64 N,
-                    hipStream_t st) {
+                    hipStream_t st, bool w_q8 = false) {
   StageTimer tm(POETX_STAGE_DENSE, st);
-  if (use_mfma(dtype) && mfma_dense_supported(n, m, N)) mfma_dense(trans_w, W, n, m, act, out, N, st);
+  if (w_q8) mfma_dense_q8(trans_w, W, n, m, act, out, N, st);
+  else if (use_mfma(dtype) && mfma_dense_supported(n, m, N)) mfma_dense(trans_w, W, n, m, act, out, N, st);
   else fma_dense(dtype, trans_w, W, n, m, act, out, N, st);
+}
+
+// POET-XQ: can the dense kernels read the 8-bit weight directly (conversion inside the operand path)?
+// Otherwise the weight is dequantised into the workspace before each product.
+bool weight_in_kernel(const poetx_linear_desc* d) {
+  return (d->flags & POETX_FLAG_W_INT8) && use_mfma(d->dtype) && mfma_dense_q8_supported(d->d_out, d->d_in, d->n_tokens);
 }
 
 size_t blockgrad_ws_bytes(int dtype, int d, i64 N, int b) {
@@ -222,8 +230,8 @@ int poetx_perm_validate(const int32_t* perm, int32_t d, int32_t* scratch, void* 
 
 // The weight the dense product reads: W itself, or its dequantised copy made at `scratch`.
 static const void* resolve_weight(const poetx_linear_desc* desc, const void* W, void* scratch, hipStream_t st) {
-  if (!(desc->flags & POETX_FLAG_W_INT8)) return W;
-  StageTimer tm(POETX_STAGE_DENSE, st);   // timed with the product it feeds
+  if (!(desc->flags & POETX_FLAG_W_INT8) || weight_in_kernel(desc)) return W;
+  StageTimer tm(POETX_STAGE_DEQUANT, st);
   weight_dequantize_q8_launch(W, desc->d_out, desc->d_in, desc->dtype, scratch, st);
   return scratch;
 }
@@ -285,7 +293,8 @@ static size_t core_workspace_bytes(const poetx_linear_desc* desc) {
   size_t N = (size_t)desc->n_tokens;
   size_t fwd = align256((size_t)desc->d_in * N * es);   // A = R^T X
   if (desc->flags & POETX_FLAG_RECOMPUTE_B) fwd += align256((size_t)desc->d_out * N * es);  // B lives here too
-  const size_t wdeq = (desc->flags & POETX_FLAG_W_INT8) ? align256((size_t)desc->d_out * desc->d_in * es) : 0;
+  const size_t wdeq = ((desc->flags & POETX_FLAG_W_INT8) && !weight_in_kernel(desc))
+                          ? align256((size_t)desc->d_out * desc->d_in * es) : 0;   // dequantised copy, only where no kernel converts on the fly
   fwd += wdeq;                                          // dequantised weight behind A (and B)
   size_t bwi = align256((size_t)desc->d_out * N * es) + wdeq;  // dB = P dZ
   int dmax = desc->d_in > desc->d_out ? desc->d_in : desc->d_out;
@@ -336,7 +345,7 @@ int poetx_linear_fwd(const poetx_linear_desc* desc, const void* X, const void* W
   }
   W = resolve_weight(desc, W, after, st);
   apply_left_dispatch(dt, X, A, m, N, N, perm_R, blocks_R, b, 1, st);        // mm1: A = R^T X
-  dense_dispatch(dt, 0, W, n, m, A, saved_B, N, st);                        // mm2: B = W A
+  dense_dispatch(dt, 0, W, n, m, A, saved_B, N, st, weight_in_kernel(desc));                        // mm2: B = W A
   apply_left_dispatch(dt, saved_B, Z, n, N, N, perm_P, blocks_P, b, 1, st);  // mm3: Z = P^T B
   lay.finish();
   return launch_status();
@@ -355,7 +364,7 @@ int poetx_linear_recompute_b(const poetx_linear_desc* desc, const void* X, const
   X = lay.in(X, m);
   W = resolve_weight(desc, W, (char*)ws + align256((size_t)m * N * esize(dt)), st);
   apply_left_dispatch(dt, X, ws, m, N, N, perm_R, blocks_R, b, 1, st);  // A = R^T X
-  dense_dispatch(dt, 0, W, n, m, ws, B_out, N, st);                    // B = W A
+  dense_dispatch(dt, 0, W, n, m, ws, B_out, N, st, weight_in_kernel(desc));                    // B = W A
   return launch_status();
 }
 
@@ -368,7 +377,7 @@ static void bwd_input_impl(const poetx_linear_desc* desc, const void* dZ, const 
   void* dB = ws;
   W = resolve_weight(desc, W, (char*)ws + align256((size_t)n * N * esize(dt)), st);
   apply_left_dispatch(dt, dZ, dB, n, N, N, perm_P, blocks_P, b, 0, st);  // dB = P dZ
-  dense_dispatch(dt, 1, W, n, m, dB, dA, N, st);                        // dA = W^T dB
+  dense_dispatch(dt, 1, W, n, m, dB, dA, N, st, weight_in_kernel(desc));                        // dA = W^T dB
   apply_left_dispatch(dt, dA, dX, m, N, N, perm_R, blocks_R, b, 0, st);  // dX = R dA
 }
 
@@ -541,7 +550,7 @@ int poetx_linear_bwd(const poetx_linear_desc* desc, const void* X, const void* d
     mfma_apply_grad(dZ, saved_B, dB, n, N, N, perm_P, blocks_P, 0, dG_P, part, st);
   }
   W = resolve_weight(desc, W, part, st);   // the P side's partials are reduced by now (stream order): same space
-  dense_dispatch(dt, 1, W, n, m, dB, dA, N, st);
+  dense_dispatch(dt, 1, W, n, m, dB, dA, N, st, weight_in_kernel(desc));
   {
     StageTimer tm(POETX_STAGE_APPLY_GRAD, st);
     mfma_apply_grad(dA, X, dX, m, N, N, perm_R, blocks_R, 0, dG_R, part, st);

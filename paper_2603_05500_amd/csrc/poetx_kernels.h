@@ -52,6 +52,9 @@ void perm_validate_launch(const int32_t* perm, int d, int32_t* scratch, hipStrea
 bool mfma_dense_supported(int n, int m, i64 N);
 void mfma_dense(int trans_w, const void* W, int n, int m, const void* act, void* out, i64 N,
                 hipStream_t st);
+// the same products on a quantised weight buffer (codes + row scales), dequantised inside the kernel (mfma_dense_q8.hip)
+bool mfma_dense_q8_supported(int n, int m, i64 N);
+void mfma_dense_q8(int trans_w, const void* Wq, int n, int m, const void* act, void* out, i64 N, hipStream_t st);
 bool mfma_apply_left_supported(int d, i64 cols, i64 ld, int b);
 void mfma_apply_left(const void* V, void* out, int d, i64 cols, i64 ld, const int32_t* perm,
                      const void* E, int b, int transpose_G, hipStream_t st);

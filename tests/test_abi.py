@@ -81,7 +81,11 @@ def test_flag_and_quantised_weight_checks(clib):
     unknown = px.make_desc(256, 512, 32, 4, 512, px.BF16, flags=8)
     w_plain, w_mem, w_xq = (px.poetx_linear_workspace_bytes(d) for d in (plain, mem, xq))
     assert w_mem >= (256 + 512) * 512 * 2 and w_mem >= w_plain
-    assert w_xq >= w_mem and w_xq >= (256 + 512) * 512 * 2 + 512 * 256 * 2     # + one dequantised weight
+    # these shapes are covered by the product kernel that converts the codes itself: no dequantised weight
+    assert w_xq == w_mem
+    # a shape it does not cover keeps room for one dequantised weight behind the activations
+    xq2 = px.make_desc(96, 160, 32, 4, 512, px.BF16, flags=px.FLAG_RECOMPUTE_B | px.FLAG_W_INT8)
+    assert px.poetx_linear_workspace_bytes(xq2) >= (96 + 160) * 512 * 2 + 160 * 96 * 2
     assert px.poetx_linear_workspace_bytes(only_q) == 0                          # INT8 weight needs the no-activation variant
     assert px.poetx_linear_workspace_bytes(unknown) == 0
     assert clib.poetx_linear_fwd(ctypes.byref(only_q), *([fake] * 9), 1 << 30, None) == 1

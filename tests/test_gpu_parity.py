@@ -410,7 +410,8 @@ def test_weight_q8_codes_bit_exact(lib, n, m, dtype):
 
 
 @pytest.mark.parametrize("m,n,N,b,k,dtype", [(256, 512, 256, 256, 4, "bf16"), (1376, 512, 384, 64, 4, "bf16"),
-                                             (96, 160, 128, 32, 3, "f32")])
+                                             (96, 160, 128, 32, 3, "f32"), (512, 768, 512, 256, 5, "bf16"),
+                                             (1024, 256, 1280, 256, 3, "bf16"), (768, 2048, 768, 256, 2, "bf16")])
 def test_xq_layer(lib, m, n, N, b, k, dtype):
     """Memory-saving variant on an INT8 base weight: every product must be the oracle's on the
     dequantised weight scale_i * q[i][k] (the oracle quantises with its own routine)."""
@@ -436,8 +437,12 @@ def test_xq_layer(lib, m, n, N, b, k, dtype):
     desc = lib.make_desc(m, n, b, k, N, code, flags=lib.FLAG_RECOMPUTE_B | lib.FLAG_W_INT8)
     plain = lib.make_desc(m, n, b, k, N, code, flags=lib.FLAG_RECOMPUTE_B)
     es = 4 if dtype == "f32" else 2
-    assert lib.poetx_linear_workspace_bytes(desc) >= lib.poetx_linear_workspace_bytes(plain)
-    assert lib.poetx_linear_workspace_bytes(desc) >= (m + n) * N * es + n * m * es
+    in_kernel = dtype == "bf16" and m % 256 == 0 and n % 256 == 0 and N % 256 == 0
+    if in_kernel:   # the dense kernels convert the codes themselves: no room for a high-precision weight
+        assert lib.poetx_linear_workspace_bytes(desc) == lib.poetx_linear_workspace_bytes(plain)
+    else:           # dequantised copy in the workspace
+        assert lib.poetx_linear_workspace_bytes(desc) >= lib.poetx_linear_workspace_bytes(plain)
+        assert lib.poetx_linear_workspace_bytes(desc) >= (m + n) * N * es + n * m * es
     ws = ws_tensor(lib.poetx_linear_workspace_bytes(desc))
     Z = torch.empty((n, N), dtype=dt, device="cuda")
     B = torch.empty((n, N), dtype=dt, device="cuda")
@@ -451,6 +456,25 @@ def test_xq_layer(lib, m, n, N, b, k, dtype):
     res = {"G_R": G_R, "G_P": G_P, "Z": to_np(Z), "B": to_np(B), "dX": to_np(dX), "dtheta_R": to_np(dR),
            "dtheta_P": to_np(dP)}
     check_layer(res, ref, data["pi_P"], dtype)
+    # The same layer on the explicitly dequantised weight (stand-alone dequantiser + plain memory-saving
+    # variant): the in-kernel conversion rounds the same way, so every output is the same bit for bit.
+    Wd = torch.empty((n, m), dtype=dt, device="cuda")
+    lib.poetx_weight_dequantize_q8(Wq, Wd)
+    wsp = ws_tensor(lib.poetx_linear_workspace_bytes(plain))
+    Z2, B2 = torch.empty_like(Z), torch.empty_like(B)
+    dX2, dA2 = torch.empty_like(dX), torch.empty_like(dA)
+    lib.poetx_linear_fwd(plain, X, Wd, pi_R, pi_P, blk_R, blk_P, Z2, None, wsp)
+    lib.poetx_linear_bwd_input(plain, dZ, Wd, pi_R, pi_P, blk_R, blk_P, dX2, dA2, wsp)
+    lib.poetx_linear_recompute_b(plain, X, Wd, pi_R, blk_R, B2, wsp)
+    torch.cuda.synchronize()
+    assert torch.equal(Z2, Z) and torch.equal(B2, B) and torch.equal(dX2, dX) and torch.equal(dA2, dA)
+    # one-call backward on the quantised weight
+    dX3 = torch.full_like(dX, float("nan"))
+    dR3, dP3 = torch.full_like(th_R, float("nan")), torch.full_like(th_P, float("nan"))
+    lib.poetx_linear_bwd(desc, X, dZ, B, Wq, pi_R, pi_P, blk_R, blk_P, th_R, th_P, dX3, dR3, dP3, False, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dX3, dX)
+    assert rel_err(to_np(dR3), ref["dtheta_R"]) <= TOL[dtype] and rel_err(to_np(dP3), ref["dtheta_P"]) <= TOL[dtype]
 
 
 # ------------------------------------------------------------------ stream capture
