@@ -192,7 +192,9 @@ def micro(args, torch, px):
         def merge():
             px.poetx_perm_blockdiag_apply_left(W, T1, pP, EP, b, True)
             px.poetx_perm_blockdiag_apply_right(T1, T2, pR, ER, b, True)
-        out["merge"].append({"out": n, "in": m, "ms": time_call(torch, merge, it)})
+        wsm = torch.empty(px.poetx_merge_workspace_bytes(n, m, px.BF16), dtype=torch.uint8, device="cuda")
+        out["merge"].append({"out": n, "in": m, "ms_apply_left_then_right": time_call(torch, merge, it),
+                             "ms_merge_weight": time_call(torch, lambda: px.poetx_merge_weight(W, T2, pR, pP, ER, EP, b, wsm), it)})
     for bb in (256, 512):                    # Cayley-Neumann table: number of blocks sweep, k = 3
         for nb in (64, 128, 192, 256, 320):
             d = nb * bb

@@ -35,11 +35,27 @@
  *  - bf16 buffers hold raw 16-bit patterns (uint16_t); accumulation is fp32.
  *  - All data pointers are DEVICE pointers unless marked host.  `stream` is a
  *    hipStream_t passed as void* (NULL = the null stream).  The caller owns
- *    every buffer; the library allocates no device memory, keeps no state
- *    between calls, enqueues its kernels on `stream` and returns without
- *    synchronising (poetx_perm_validate excepted).  `ws` is scratch of at least
- *    the size the matching *_workspace_bytes call reports, 256-byte aligned.
- *  - Output buffers must not overlap input buffers.
+ *    every buffer; the library allocates no device memory, enqueues its kernels
+ *    on `stream` and returns without synchronising (poetx_perm_validate
+ *    excepted).  No call leaves anything behind that a later call depends on;
+ *    the only process-wide state is the two diagnostic switches
+ *    (poetx_debug_force_fma, poetx_profile_begin/end, both off by default), the
+ *    static scratch of poetx_cnp_build_static, and once-only kernel attributes.
+ *    `ws` is scratch of at least the size the matching *_workspace_bytes call
+ *    reports, 256-byte aligned.
+ *  - Alignment: bf16 tensors, block storage and workspaces should be 16-byte aligned
+ *    with leading dimensions that are multiples of 8 elements (what any device
+ *    allocator gives).  The matrix-core kernels move 16 bytes per lane; a call
+ *    whose pointers are not so aligned runs on the plain fp32-FMA kernels.
+ *  - Which kernels serve a shape: the matrix-core kernels cover bf16 tensors with
+ *    b = 256 or 512 dividing d_in and d_out, dimensions that are multiples of 256
+ *    and token counts that are multiples of 256; everything else (fp32 tensors,
+ *    small blocks, ragged tails) runs on plain fp32-FMA kernels, correct but one to
+ *    two orders of magnitude slower at large sizes.  poetx_linear_path reports the
+ *    choice for a descriptor, so a caller can refuse shapes that would fall off
+ *    the fast path instead of finding out from the clock.
+ *  - Output buffers must not overlap input buffers (in-place operation is refused:
+ *    the kernels of one call read rows that other workgroups of the same call write).
  *  - Return value: POETX_OK (0) or a poetx_status error.  Arguments are checked
  *    on the host before anything is enqueued; on error nothing was launched.
  *    Permutation contents are NOT checked on the hot path (use
@@ -219,6 +235,19 @@ int poetx_perm_blockdiag_apply_right(const void* V, void* out, int64_t rows, int
                                      const int32_t* perm, const void* blocks, int32_t b,
                                      int32_t transpose_G, int32_t dtype, void* stream);
 
+/* Merge step of the outer loop (Sec. 3, after Eq. 2: every few hundred steps the learned factors are
+ * folded into the base weight, W <- R W0 P in the paper's orientation, and the parameters reset).
+ * On the stored weight W = W0^T (n x m, row major): W_out = P^T W R^T, the same result as
+ * poetx_perm_blockdiag_apply_left (P side, transpose) followed by poetx_perm_blockdiag_apply_right
+ * (R side, transpose), but with the input-side product run as a row gather on the transposed matrix,
+ * so that both sides use the streaming kernels.  W_out must not overlap W.
+ * ws: poetx_merge_workspace_bytes(n, m, dtype) bytes (two weight-sized buffers). */
+size_t poetx_merge_workspace_bytes(int32_t n, int32_t m, int32_t dtype);
+int poetx_merge_weight(const void* W, void* W_out, int32_t n, int32_t m,
+                       const int32_t* perm_R, const int32_t* perm_P,
+                       const void* blocks_R, const void* blocks_P, int32_t b, int32_t dtype,
+                       void* ws, size_t ws_bytes, void* stream);
+
 /* Debug helper: checks on the device that perm is a bijection of {0..d-1}.
  * scratch: d + 1 int32 on the device.  Synchronises `stream`. */
 int poetx_perm_validate(const int32_t* perm, int32_t d, int32_t* scratch, void* stream);
@@ -236,6 +265,18 @@ int poetx_perm_validate(const int32_t* perm, int32_t d, int32_t* scratch, void* 
  * poetx_linear_workspace_bytes: scratch needed by the largest of the linear calls.
  */
 size_t poetx_linear_workspace_bytes(const poetx_linear_desc* desc);
+
+/* Which kernel families would serve `desc` (bit set = matrix cores; 16-byte aligned pointers
+ * assumed).  Returns a combination of POETX_PATH_* bits, 0 when every stage runs on the plain
+ * fp32-FMA kernels, or minus a poetx_status when the descriptor is invalid. */
+#define POETX_PATH_APPLY 1              /* gather + block-diagonal product + scatter            */
+#define POETX_PATH_DENSE 2              /* B = W A, dA = W^T dB                                */
+#define POETX_PATH_BLOCKGRAD 4          /* block gradients (two-call backward)                 */
+#define POETX_PATH_SERIES 8             /* series backward on the matrix cores                 */
+#define POETX_PATH_SERIES_ON_CHIP 16    /* ... as one-launch chains with the block in LDS      */
+#define POETX_PATH_BWD_ONE_PASS 32      /* poetx_linear_bwd streams each side's gradient once  */
+#define POETX_PATH_W_INT8_IN_KERNEL 64  /* POETX_FLAG_W_INT8 converted inside the dense kernels */
+int poetx_linear_path(const poetx_linear_desc* desc);
 
 /* X: m x N.  W: n x m.  blocks_R / blocks_P: block storage of the dtype (see top)
  * with ceil(m/b) and ceil(n/b) blocks.

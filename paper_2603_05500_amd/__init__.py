@@ -25,8 +25,8 @@ FEATURE_MAJOR, TOKEN_MAJOR = 0, 1
 EXPORTS = (
     "poetx_status_string", "poetx_version", "poetx_debug_force_fma",
     "poetx_cnp_workspace_bytes", "poetx_cnp_build", "poetx_cnp_build_static", "poetx_cnp_bwd_workspace_bytes", "poetx_cnp_bwd",
-    "poetx_perm_blockdiag_apply_left", "poetx_perm_blockdiag_apply_right", "poetx_perm_validate",
-    "poetx_linear_workspace_bytes", "poetx_linear_fwd", "poetx_linear_bwd_input", "poetx_linear_bwd_skew",
+    "poetx_perm_blockdiag_apply_left", "poetx_perm_blockdiag_apply_right", "poetx_perm_validate", "poetx_merge_workspace_bytes", "poetx_merge_weight",
+    "poetx_linear_workspace_bytes", "poetx_linear_path", "poetx_linear_fwd", "poetx_linear_bwd_input", "poetx_linear_bwd_skew",
     "poetx_linear_recompute_b", "poetx_linear_bwd",
     "poetx_weight_q8_bytes", "poetx_weight_quantize_q8", "poetx_weight_dequantize_q8",
     "poetx_profile_begin", "poetx_profile_end",
@@ -84,10 +84,17 @@ def load_library(path: str | None = None):
     lib.poetx_perm_blockdiag_apply_right.restype = c_int
     lib.poetx_perm_blockdiag_apply_right.argtypes = [c_void_p, c_void_p, c_int64, c_int32, c_int64, c_void_p,
                                                      c_void_p, c_int32, c_int32, c_int32, c_void_p]
+    lib.poetx_merge_workspace_bytes.restype = c_size_t
+    lib.poetx_merge_workspace_bytes.argtypes = [c_int32, c_int32, c_int32]
+    lib.poetx_merge_weight.restype = c_int
+    lib.poetx_merge_weight.argtypes = [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
+                                       c_int32, c_int32, c_void_p, c_size_t, c_void_p]
     lib.poetx_perm_validate.restype = c_int
     lib.poetx_perm_validate.argtypes = [c_void_p, c_int32, c_void_p, c_void_p]
     lib.poetx_linear_workspace_bytes.restype = c_size_t
     lib.poetx_linear_workspace_bytes.argtypes = [POINTER(LinearDesc)]
+    lib.poetx_linear_path.restype = c_int
+    lib.poetx_linear_path.argtypes = [POINTER(LinearDesc)]
     lib.poetx_linear_fwd.restype = c_int
     lib.poetx_linear_fwd.argtypes = [POINTER(LinearDesc)] + [c_void_p] * 9 + [c_size_t, c_void_p]
     lib.poetx_linear_bwd_input.restype = c_int
@@ -206,6 +213,17 @@ def poetx_perm_blockdiag_apply_right(V, out, perm, blocks, b, transpose_G):
            "poetx_perm_blockdiag_apply_right")
 
 
+def poetx_merge_workspace_bytes(n: int, m: int, dtype: int) -> int:
+    return load_library().poetx_merge_workspace_bytes(n, m, dtype)
+
+
+def poetx_merge_weight(W, W_out, perm_R, perm_P, blocks_R, blocks_P, b, ws):
+    n, m = W.shape
+    _check(load_library().poetx_merge_weight(_ptr(W), _ptr(W_out), n, m, _ptr(perm_R), _ptr(perm_P), _ptr(blocks_R),
+                                             _ptr(blocks_P), b, dtype_code(W), _ptr(ws), _ws_bytes(ws), _stream()),
+           "poetx_merge_weight")
+
+
 def poetx_perm_validate(perm, scratch) -> bool:
     """True if perm is a bijection; False if the library reports BAD_PERM."""
     lib = load_library()
@@ -218,6 +236,15 @@ def poetx_perm_validate(perm, scratch) -> bool:
 
 def _ws_bytes(ws):
     return ws.numel() * ws.element_size()
+
+
+PATH_APPLY, PATH_DENSE, PATH_BLOCKGRAD, PATH_SERIES, PATH_SERIES_ON_CHIP, PATH_BWD_ONE_PASS, PATH_W_INT8_IN_KERNEL = \
+    1, 2, 4, 8, 16, 32, 64
+
+
+def poetx_linear_path(desc) -> int:
+    """Bit mask of the stages the matrix-core kernels serve for `desc` (negative: invalid descriptor)."""
+    return load_library().poetx_linear_path(ctypes.byref(desc))
 
 
 def poetx_linear_fwd(desc, X, W, perm_R, perm_P, blocks_R, blocks_P, Z, saved_B, ws):

@@ -5,8 +5,9 @@
 // cover.  Every step is one instance of a small LDS-tiled batched product
 //     C[batch](i, j) = sum_k A[batch](i, k) * B[batch](k, j)
 // whose operands are described by accessor structs, so gather-by-permutation,
-// scatter-by-permutation, on-the-fly skew construction and the packed-gradient
-// projection are all fused into the loads and stores.
+// scatter-by-permutation and on-the-fly skew construction are fused into the loads
+// and stores.  The projection of the series gradient onto the packed parameters is a
+// separate element-wise kernel (skew_project_kernel), shared with the matrix-core path.
 #include "poetx_kernels.h"
 
 namespace poetx {
@@ -267,6 +268,11 @@ __global__ void skew_project_kernel(const float* M, int b, int d, int nb, float*
   *dst = accumulate ? *dst + v : v;
 }
 
+__global__ void zero_i32_kernel(int32_t* p, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
 __global__ void perm_mark_kernel(const int32_t* perm, int d, int32_t* scratch) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= d) return;
@@ -403,7 +409,7 @@ void skew_project_launch(const float* M, int b, int d, float* dtheta, int accumu
 }
 
 void perm_validate_launch(const int32_t* perm, int d, int32_t* scratch, hipStream_t st) {
-  (void)hipMemsetAsync(scratch, 0, sizeof(int32_t) * ((size_t)d + 1), st);
+  hipLaunchKernelGGL(zero_i32_kernel, dim3(ceil_div(d + 1, 256)), dim3(256), 0, st, scratch, d + 1);
   hipLaunchKernelGGL(perm_mark_kernel, dim3(ceil_div(d, 256)), dim3(256), 0, st, perm, d, scratch);
 }
 

@@ -330,11 +330,10 @@ void launch_apply_stream(const uint16_t* V, uint16_t* out, int d, i64 cols, i64 
   constexpr size_t LDS = 2 * (size_t)B * BN * 2 + 8 * 4096;   // 2-stage ring + per-wave output staging
   constexpr int MSPLIT = B / 256;
   auto kern = apply_left_stream_kernel<B, BN>;
-  static bool configured = false;
-  if (!configured) {
-    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
-    configured = true;
-  }
+  // once per kernel instance; a function-local static is initialised exactly once, whichever thread gets there first
+  static const bool configured =
+      hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS) == hipSuccess;
+  (void)configured;
   const int nb = d / B, tiles = (int)(cols / BN);
   const int chunks = stream_chunks(nb * MSPLIT, tiles);
   hipLaunchKernelGGL(kern, dim3(chunks * MSPLIT, nb), dim3(512), LDS, st, V, out, ld, perm, E, trans, tiles / chunks);
@@ -349,11 +348,10 @@ void launch_apply(const uint16_t* V, uint16_t* out, int d, i64 cols, i64 ld, con
                   int trans, hipStream_t st) {
   constexpr size_t LDS = (size_t)B * (BN + PAD_T) * sizeof(uint16_t);
   auto kern = apply_left_bf16_kernel<B, BN>;
-  static bool configured = false;
-  if (!configured) {
-    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS);
-    configured = true;
-  }
+  // once per kernel instance; a function-local static is initialised exactly once, whichever thread gets there first
+  static const bool configured =
+      hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS) == hipSuccess;
+  (void)configured;
   hipLaunchKernelGGL(kern, dim3((unsigned)(cols / BN), d / B), dim3(256), LDS, st, V, out, ld, perm, E, trans);
 }
 

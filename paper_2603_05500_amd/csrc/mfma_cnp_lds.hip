@@ -297,11 +297,10 @@ __global__ __launch_bounds__(256) void cnp_chain_kernel(ChainArgs a) {
 template <int MODE>
 void launch_chain(const ChainArgs& a, hipStream_t st) {
   auto kern = cnp_chain_kernel<MODE>;
-  static bool configured = false;
-  if (!configured) {
-    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, CHAIN_LDS);
-    configured = true;
-  }
+  // once per kernel instance; a function-local static is initialised exactly once, whichever thread gets there first
+  static const bool configured =
+      hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, CHAIN_LDS) == hipSuccess;
+  (void)configured;
   hipLaunchKernelGGL(kern, dim3(LB / 128, a.nb), dim3(256), CHAIN_LDS, st, a);
 }
 

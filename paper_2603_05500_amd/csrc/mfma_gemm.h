@@ -371,11 +371,10 @@ template <int BM, int BN, int WGM, int WGN, bool A_KMAJOR, bool B_KMAJOR, bool G
 void launch(const Args& g, Epi epi, int batches, int splits, hipStream_t st) {
   using C = Cfg<BM, BN, WGM, WGN, NS>;
   auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, A_KMAJOR, B_KMAJOR, GATHER, NS, EXACT_TAIL, Epi>;
-  static bool configured = false;
-  if (!configured) {
-    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
-    configured = true;
-  }
+  // once per kernel instance; a function-local static is initialised exactly once, whichever thread gets there first
+  static const bool configured =
+      hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES) == hipSuccess;
+  (void)configured;
   hipLaunchKernelGGL(kern, dim3(g.tiles_m * g.tiles_n, batches, splits), dim3(64 * WGM * WGN), C::LDS_BYTES, st, g, epi);
 }
 

@@ -37,6 +37,8 @@ int static_scratch(void** out) {
 }
 
 inline bool use_mfma(int dtype) { return dtype == POETX_BF16 && !g_force_fma.load(); }
+// the matrix-core kernels move 16 bytes per lane: every tensor they touch must be 16-byte aligned
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 inline size_t esize(int dtype) { return dtype == POETX_F32 ? 4 : 2; }
 inline bool dtype_ok(int dtype) { return dtype == POETX_F32 || dtype == POETX_BF16; }
 inline bool overlap(const void* a, size_t na, const void* b, size_t nb) {
@@ -75,7 +77,7 @@ size_t cnp_bwd_ws_floats_both(int m, int n, int b, int k) {
 void apply_left_dispatch(int dtype, const void* V, void* out, int d, i64 cols, i64 ld, const int32_t* perm,
                          const void* blocks, int b, int trans, hipStream_t st) {
   StageTimer tm(POETX_STAGE_APPLY, st);
-  if (use_mfma(dtype) && mfma_apply_left_supported(d, cols, ld, b))
+  if (use_mfma(dtype) && mfma_apply_left_supported(d, cols, ld, b) && aligned16(V) && aligned16(out) && aligned16(blocks))
     mfma_apply_left(V, out, d, cols, ld, perm, blocks, b, trans, st);
   else
     fma_apply_left(dtype, V, out, d, cols, ld, perm, blocks, b, trans, st);
@@ -86,7 +88,8 @@ void dense_dispatch(int dtype, int trans_w, const void* W, int n, int m, const v
                     hipStream_t st, bool w_q8 = false) {
   StageTimer tm(POETX_STAGE_DENSE, st);
   if (w_q8) mfma_dense_q8(trans_w, W, n, m, act, out, N, st);
-  else if (use_mfma(dtype) && mfma_dense_supported(n, m, N)) mfma_dense(trans_w, W, n, m, act, out, N, st);
+  else if (use_mfma(dtype) && mfma_dense_supported(n, m, N) && aligned16(W) && aligned16(act) && aligned16(out))
+    mfma_dense(trans_w, W, n, m, act, out, N, st);
   else fma_dense(dtype, trans_w, W, n, m, act, out, N, st);
 }
 
@@ -218,6 +221,39 @@ int poetx_perm_blockdiag_apply_right(const void* V, void* out, int64_t rows, int
   return launch_status();
 }
 
+size_t poetx_merge_workspace_bytes(int32_t n, int32_t m, int32_t dtype) {
+  if (n <= 0 || m <= 0 || !dtype_ok(dtype)) return 0;
+  return 2 * align256((size_t)n * m * esize(dtype));
+}
+
+int poetx_merge_weight(const void* W, void* W_out, int32_t n, int32_t m, const int32_t* perm_R, const int32_t* perm_P,
+                       const void* blocks_R, const void* blocks_P, int32_t b, int32_t dtype, void* ws, size_t ws_bytes,
+                       void* stream) {
+  if (!W || !W_out || !perm_R || !perm_P || !blocks_R || !blocks_P || n <= 0 || m <= 0 || b <= 0 || !dtype_ok(dtype))
+    return POETX_ERR_INVALID_ARG;
+  if (b > n || b > m) return POETX_ERR_BAD_SHAPE;
+  const size_t bytes = (size_t)n * m * esize(dtype);
+  if (overlap(W, bytes, W_out, bytes)) return POETX_ERR_INVALID_ARG;
+  if (!ws || ws_bytes < poetx_merge_workspace_bytes(n, m, dtype)) return POETX_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  void* T1 = ws;
+  void* T2 = (char*)ws + align256(bytes);
+  // W (n x m) is feature major for the output side (rows = output features): P^T W is a left apply.
+  // The input side acts on the columns; a column gather is a row gather of the transpose, so the
+  // product with R^T runs as R (P^T W)^T on the transposed matrix and is transposed back.
+  apply_left_dispatch(dtype, W, T1, n, m, m, perm_P, blocks_P, b, 1, st);        // T1 = P^T W         (n x m)
+  {
+    StageTimer tm(POETX_STAGE_LAYOUT, st);
+    transpose_launch(dtype, T1, T2, n, m, st);                                   // T2 = T1^T          (m x n)
+  }
+  apply_left_dispatch(dtype, T2, T1, m, n, n, perm_R, blocks_R, b, 0, st);       // T1 = R T2          (m x n)
+  {
+    StageTimer tm(POETX_STAGE_LAYOUT, st);
+    transpose_launch(dtype, T1, W_out, m, n, st);                                // W_out = (R T2)^T = P^T W R^T
+  }
+  return launch_status();
+}
+
 int poetx_perm_validate(const int32_t* perm, int32_t d, int32_t* scratch, void* stream) {
   if (!perm || !scratch || d <= 0) return POETX_ERR_INVALID_ARG;
   hipStream_t st = (hipStream_t)stream;
@@ -248,6 +284,27 @@ static size_t core_workspace_bytes(const poetx_linear_desc* desc);
 size_t poetx_linear_workspace_bytes(const poetx_linear_desc* desc) {
   if (check_desc(desc) != POETX_OK) return 0;
   return core_workspace_bytes(desc) + layout_staging_bytes(desc);
+}
+
+int poetx_linear_path(const poetx_linear_desc* d) {
+  const int rc = check_desc(d);
+  if (rc) return -rc;
+  const int m = d->d_in, n = d->d_out, b = d->block;
+  const i64 N = d->n_tokens;
+  int path = 0;
+  if (!use_mfma(d->dtype)) return path;
+  if (mfma_apply_left_supported(m, N, N, b) && mfma_apply_left_supported(n, N, N, b)) path |= POETX_PATH_APPLY;
+  if (mfma_dense_supported(n, m, N)) path |= POETX_PATH_DENSE;
+  if (mfma_blockgrad_supported(m, N, b) && mfma_blockgrad_supported(n, N, b)) path |= POETX_PATH_BLOCKGRAD;
+  if (d->cnp_precision == POETX_CNP_BF16 && mfma_cnp_supported(m, b) && mfma_cnp_supported(n, b)) {
+    path |= POETX_PATH_SERIES;
+    if (lds_cnp_supported(m, b) && lds_cnp_supported(n, b)) path |= POETX_PATH_SERIES_ON_CHIP;
+    if (lds_cnp_supported(m, b) && lds_cnp_supported(n, b) && mfma_apply_grad_supported(m, N, N, b) &&
+        mfma_apply_grad_supported(n, N, N, b))
+      path |= POETX_PATH_BWD_ONE_PASS;
+  }
+  if (weight_in_kernel(d)) path |= POETX_PATH_W_INT8_IN_KERNEL;
+  return path;
 }
 
 // Feature-major <-> token-major copies around a call.  in(): the feature-major copy of a

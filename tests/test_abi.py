@@ -97,3 +97,17 @@ def test_flag_and_quantised_weight_checks(clib):
     assert clib.poetx_weight_quantize_q8(None, px.BF16, 8, 8, fake, None) == 1
     assert clib.poetx_weight_quantize_q8(fake, 5, 8, 8, fake, None) == 1
     assert clib.poetx_weight_dequantize_q8(fake, 8, 0, px.BF16, fake, None) == 1
+
+
+def test_linear_path_query(clib):
+    """poetx_linear_path tells which stages the matrix-core kernels serve: all of them for the benchmark
+    shapes, none for fp32 tensors or small blocks, and the INT8 bit only with the flag."""
+    full = px.PATH_APPLY | px.PATH_DENSE | px.PATH_BLOCKGRAD | px.PATH_SERIES | px.PATH_SERIES_ON_CHIP | px.PATH_BWD_ONE_PASS
+    assert px.poetx_linear_path(px.make_desc(4096, 14336, 256, 5, 16384, px.BF16)) == full
+    b512 = px.poetx_linear_path(px.make_desc(4096, 1024, 512, 5, 16384, px.BF16))
+    assert b512 == px.PATH_APPLY | px.PATH_DENSE | px.PATH_BLOCKGRAD | px.PATH_SERIES
+    assert px.poetx_linear_path(px.make_desc(256, 256, 32, 4, 512, px.F32)) == 0
+    assert px.poetx_linear_path(px.make_desc(512, 1376, 64, 4, 1024, px.BF16)) == 0
+    xq = px.make_desc(4096, 4096, 256, 5, 16384, px.BF16, flags=px.FLAG_RECOMPUTE_B | px.FLAG_W_INT8)
+    assert px.poetx_linear_path(xq) == full | px.PATH_W_INT8_IN_KERNEL
+    assert px.poetx_linear_path(px.make_desc(256, 256, 32, 0, 512, px.F32)) == -1     # k < 1

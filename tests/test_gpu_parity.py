@@ -313,7 +313,8 @@ def test_kernel_family_boundaries(lib, N):
 
 
 # ------------------------------------------------------------------ merge step W <- R W P
-@pytest.mark.parametrize("m,n,b,dtype", [(256, 512, 256, "bf16"), (96, 160, 32, "f32"), (1376, 512, 64, "bf16")])
+@pytest.mark.parametrize("m,n,b,dtype", [(256, 512, 256, "bf16"), (96, 160, 32, "f32"), (1376, 512, 64, "bf16"),
+                                         (1024, 768, 256, "bf16")])
 def test_merge_step(lib, m, n, b, dtype):
     """The periodic merge (Sec. 3, after Eq. 2): W_i = R W_{i-1} P.  On the stored weight W = W0^T this is
     W_new = P^T W R^T = apply_right(apply_left(W, P^T), R^T); checked against the dense definition, and
@@ -339,6 +340,12 @@ def test_merge_step(lib, m, n, b, dtype):
     assert rel_err(to_np(Wn), W_eff.T) <= TOL[dtype]
     # mergeability: plain product with the merged weight == POET-X forward with the factors
     assert rel_err(to_np(Wn) @ X, Zd) <= 2 * TOL[dtype]
+    # the merge entry point (both sides through the left-apply kernels): same matrix
+    Wm = torch.full_like(Wd, float("nan"))
+    wsm = ws_tensor(lib.poetx_merge_workspace_bytes(n, m, lib.F32 if dtype == "f32" else lib.BF16))
+    lib.poetx_merge_weight(Wd, Wm, pR, pP, blk_R, blk_P, b, wsm)
+    torch.cuda.synchronize()
+    assert rel_err(to_np(Wm), W_eff.T) <= TOL[dtype] and row_rel_err(to_np(Wm), W_eff.T) <= TOL[dtype]
 
 
 # ------------------------------------------------------------------ memory-saving variant
