@@ -22,7 +22,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 # L2<->fabric bytes per dense launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by
 # what the same counters read for a 1 GiB copy (2.0 and 1.0); see profiles/llama8b_b256_layer_counters.md.
-DENSE_TRAFFIC_BYTES_PER_LAUNCH = {"llama8b-b256": 1.69e9}
+DENSE_TRAFFIC_BYTES_PER_LAUNCH = {"llama8b-b256": 1.76e9}
 
 
 def parse():
@@ -33,7 +33,8 @@ def parse():
     ap.add_argument("--workload", default="llama8b-b256",
                     help="llama8b-b256 (default, the metric's configuration), llama8b-b512, llama3b (fresh "
                          "permutations every step), llama1b; or `micro`: the shapes of the paper's kernel tables "
-                         "(permutation, block-diagonal product, Cayley-Neumann build) on the library's entry points")
+                         "(permutation, block-diagonal product, Cayley-Neumann build) on the library's entry points; "
+                         "or `vendor-gemm`: torch.matmul on the layer's dense shapes, as a reference for the dense kernel")
     ap.add_argument("--variant", default="fast", choices=["fast", "mem", "xq"],
                     help="fast keeps B from the forward pass (the measured metric); mem recomputes it in backward; "
                          "xq is mem on an INT8 base weight that every dense product dequantises first")
@@ -46,6 +47,7 @@ def parse():
     ap.add_argument("--two-call-backward", action="store_true",
                     help="run the backward pass as poetx_linear_bwd_input + poetx_linear_bwd_skew instead of the "
                          "single poetx_linear_bwd call")
+    ap.add_argument("--no-b512", action="store_true", help="skip the short llama8b-b512 pass that the default run appends")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=128, help="tokens in the oracle's timed sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -170,12 +172,21 @@ def micro(args, torch, px):
     b = 256
 
     def apply_case(d, N):
-        V = torch.randn((d, N), generator=g, device="cuda").to(torch.bfloat16)
-        O = torch.empty_like(V)
+        # The calls rotate through enough input / output pairs that their combined footprint (>= 800 MB,
+        # at least 3 pairs) is several times the 256 MB Infinity Cache: the figures are HBM figures.
+        sets = max(3, -(-800_000_000 // (4 * d * N)))
+        Vs = [torch.randn((d, N), generator=g, device="cuda").to(torch.bfloat16) for _ in range(sets)]
+        Os = [torch.empty_like(Vs[0]) for _ in range(sets)]
         E = (torch.randn((d // b, 2, b, b), generator=g, device="cuda") * 0.01).to(torch.bfloat16)
         perm = torch.randperm(d, generator=g, device="cuda").to(torch.int32)
-        ms = time_call(torch, lambda: px.poetx_perm_blockdiag_apply_left(V, O, perm, E, b, True), it)
-        return {"hidden": d, "tokens": N, "ms": ms, "GBs": 4.0 * d * N / ms / 1e6}
+        turn = [0]
+
+        def call():
+            i = turn[0] % sets
+            turn[0] += 1
+            px.poetx_perm_blockdiag_apply_left(Vs[i], Os[i], perm, E, b, True)
+        ms = time_call(torch, call, max(it, 2 * sets), warm=sets)
+        return {"hidden": d, "tokens": N, "ms": ms, "GBs": 4.0 * d * N / ms / 1e6, "buffer_pairs": sets}
 
     for d in (2048, 4096, 8192, 16384):      # permutation table: hidden size sweep
         out["apply_vs_hidden"].append(apply_case(d, 8192))
@@ -208,25 +219,8 @@ def micro(args, torch, px):
     return out
 
 
-def main():
-    args = parse()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build is single-GPU; run with --gpus 1 (no multi-GPU path exists)", file=sys.stderr)
-        sys.exit(2)
-    import torch
-    import paper_2603_05500_amd as px
-    from workloads import get_config
-
-    px.load_library()
-    if args.workload == "micro":
-        torch.cuda.set_device(0)
-        res = micro(args, torch, px)
-        print(json.dumps({"metric": "POET-X kernel microbenchmarks at the shapes of the paper's kernel tables",
-                          "unit": "ms", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
-                          "config": {"workload": "micro: fused permutation + block-diagonal apply (b=256) over hidden "
-                                                 "size and token count; Cayley-Neumann build k=3 over block count"},
-                          "micro": res}))
-        return
+def run_workload(args, torch, px, get_config):
+    """One layer workload: warm-up, the timed steps, a second pass with stage events; returns the result line's dict."""
     cfg = get_config(args.workload)
     torch.cuda.set_device(0)
     code = px.BF16 if cfg.dtype == "bf16" else px.F32
@@ -400,6 +394,67 @@ def main():
                      "frac": dense_tflops / PEAK_BF16_TFLOPS, "traffic": DENSE_TRAFFIC_BYTES_PER_LAUNCH.get(cfg.name),
                      "launches": int(dense_cnt), "avg_launch_ms": dense_ms / max(int(dense_cnt), 1)},
     }
+    return out, cfg
+
+
+def vendor_gemm(args, torch):
+    """Reference points for the dense product: the vendor GEMM behind torch.matmul on the layer's three
+    dense shapes, same value distributions, sustained (60 launches of warm-up).  NN is the layout this
+    library's products have (activations feature major); NT has both operands contraction-major."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(20260305)
+    rows = []
+    for n, m, N in ((4096, 4096, 16384), (14336, 4096, 16384), (4096, 14336, 16384)):
+        W = (torch.randn((n, m), generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+        A = torch.randn((m, N), generator=g, device="cuda").to(torch.bfloat16)
+        At = A.t().contiguous()
+        r = {"n": n, "m": m, "N": N}
+        for name, fn in (("NN", lambda: torch.matmul(W, A)), ("NT", lambda: torch.matmul(W, At.t()))):
+            ms = time_call(torch, fn, 40, warm=60)
+            r[name + "_ms"], r[name + "_TFLOPs"] = ms, 2.0 * n * m * N / ms / 1e9
+        rows.append(r)
+        del W, A, At
+    return rows
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 (no multi-GPU path exists)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2603_05500_amd as px
+    from workloads import get_config
+
+    px.load_library()
+    if args.workload == "vendor-gemm":
+        torch.cuda.set_device(0)
+        print(json.dumps({"metric": "vendor GEMM (torch.matmul) on the dense shapes of the llama8b layer", "unit": "TFLOP/s",
+                          "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": "vendor-gemm"}, "vendor_gemm": vendor_gemm(args, torch)}))
+        return
+    if args.workload == "micro":
+        torch.cuda.set_device(0)
+        res = micro(args, torch, px)
+        print(json.dumps({"metric": "POET-X kernel microbenchmarks at the shapes of the paper's kernel tables",
+                          "unit": "ms", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": "micro: fused permutation + block-diagonal apply (b=256) over hidden "
+                                                 "size and token count; Cayley-Neumann build k=3 over block count"},
+                          "micro": res}))
+        return
+    out, cfg = run_workload(args, torch, px, get_config)
+    if args.workload == "llama8b-b256" and args.variant == "fast" and not args.no_b512:
+        # config 5 names both block sizes: a short pass of the b = 512 variant rides along under its own key
+        import copy
+        import gc
+        gc.collect()
+        torch.cuda.empty_cache()
+        a2 = copy.copy(args)
+        a2.workload, a2.steps, a2.warmup = "llama8b-b512", max(3, args.steps // 3), 1
+        o2, _ = run_workload(a2, torch, px, get_config)
+        out["also"] = {"llama8b-b512": {k2: o2[k2] for k2 in ("value", "unit", "ms_per_step", "steps", "warmup",
+                                                              "mfma_peak_frac_layer", "stage_ms_per_step", "stage_rates")}}
+        out["also"]["llama8b-b512"]["workload"] = o2["config"]["workload"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_tokens)
     print(json.dumps(out))
