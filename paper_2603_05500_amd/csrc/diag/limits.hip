@@ -64,6 +64,34 @@ __global__ __launch_bounds__(256) void mfma_loop_kernel(const bf16x8* __restrict
   out[tid] = s;
 }
 
+// the same wave tile (128 x 128) out of 8 x 8 tiles of v_mfma_f32_16x16x32_bf16: twice the operand
+// register reads per flop, half the accumulator traffic
+__global__ __launch_bounds__(256) void mfma16_loop_kernel(const bf16x8* __restrict__ src, float* out, int iters) {
+  typedef float floatx4 __attribute__((ext_vector_type(4)));
+  bf16x8 a[8], b[8];
+  const int tid = blockIdx.x * 256 + threadIdx.x;
+  for (int i = 0; i < 8; ++i) a[i] = src[(size_t)(i & 3) * 65536 + ((tid + 4096 * (i >> 2)) & 65535)];
+  for (int i = 0; i < 8; ++i) b[i] = src[(size_t)(4 + (i & 3)) * 65536 + ((tid + 4096 * (i >> 2)) & 65535)];
+  floatx4 acc[8][8];
+  for (int i = 0; i < 8; ++i)
+    for (int j = 0; j < 8; ++j)
+      for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    bf16x8 t = a[0];
+    for (int i = 0; i < 7; ++i) a[i] = a[i + 1];
+    a[7] = t;
+  }
+  float s = 0;
+  for (int i = 0; i < 8; ++i)
+    for (int j = 0; j < 8; ++j)
+      for (int v = 0; v < 4; ++v) s += acc[i][j][v];
+  out[tid] = s;
+}
+
 __global__ void copy_kernel(const float4* __restrict__ in, float4* __restrict__ out, size_t n4) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -121,6 +149,8 @@ int main() {
         const float ms = sustained_ms([&] { hipLaunchKernelGGL(mfma_loop_kernel, dim3(grid), dim3(256), 0, 0, (const bf16x8*)d, out, iters); }, 12, 8);
         printf("  %-40s %d wave(s) per SIMD: %7.1f TFLOP/s\n", mode == 0 ? "operands all zero" : "operands N(0, 0.02^2) x N(0, 1)", wps,
                (double)grid * 4 * iters * 16 * 32768.0 / ms / 1e9);
+        const float ms16 = sustained_ms([&] { hipLaunchKernelGGL(mfma16_loop_kernel, dim3(grid), dim3(256), 0, 0, (const bf16x8*)d, out, iters / 2); }, 12, 8);
+        printf("  %-40s %d wave(s) per SIMD: %7.1f TFLOP/s  (16x16x32 tiles)\n", "", wps, (double)grid * 4 * (iters / 2) * 64 * 16384.0 / ms16 / 1e9);
       }
     }
     CHECK(hipFree(d));
@@ -161,6 +191,7 @@ int main() {
     time_dense<false, 1>("backward, no direct-to-LDS loads in the loop", g, flops);
     time_dense<false, 2>("backward, no fragment reads in the loop", g, flops);
     time_dense<false, 3>("backward, neither (MFMAs, barrier, epilogue only)", g, flops);
+    time_dense<false, 4>("backward, every load re-fetches the first stage (cache hits)", g, flops);
     // spot check of the unmodified kernel (forward)
     auto kern = dense::dense_stream_kernel<true, 0>;
     hipLaunchKernelGGL(kern, dim3(256), dim3(256), dense::LDS_BYTES, 0, g);

@@ -54,7 +54,8 @@ __device__ inline void dma16s(const void* sbase, uint32_t voff, uint32_t lds_add
 }
 
 // DIAG (measurement builds only; the library instantiates DIAG = 0): bit 0 stops the direct-to-LDS loads
-// after the prologue, bit 1 stops the fragment reads inside the loop -- the results are then wrong,
+// after the prologue, bit 1 stops the fragment reads inside the loop, bit 2 keeps the load addresses on
+// the first stage of the first tile (all loads hit in cache) -- the results are then wrong,
 // every address stays what it was, and the timing shows what the loads or the reads cost.
 template <bool A_KMAJOR, int DIAG = 0>
 __global__ __launch_bounds__(256) void dense_stream_kernel(DenseArgs g) {
@@ -121,6 +122,7 @@ __global__ __launch_bounds__(256) void dense_stream_kernel(DenseArgs g) {
   // of loads in flight -- and with it the vmcnt bound of the barrier -- never changes.
   auto issue_advance = [&]() {
     islot = islot + 1 == NS ? 0 : islot + 1;
+    if (DIAG & 4) return;   // every stage re-fetches the first one: the loads stay, their misses go
     if (ikt + 1 < KT) {
       ++ikt;
       Ab += stepA;
