@@ -355,13 +355,19 @@ def run_workload(args, torch, px, get_config):
 
     dense_f, block_f, cnp_f = layer_flops(cfg)
     dense_ms, dense_cnt = stages["dense"]
-    dense_tflops = dense_f * args.steps / (dense_ms * 1e-3) / 1e12 if dense_ms > 0 else 0.0
+    # the memory-saving variants run the forward product a second time in the backward pass (Sec. 3.5):
+    # the stage rates count the work executed, mfma_peak_frac_layer the algorithmic work of a step
+    recompute = args.variant != "fast"
+    dense_exec = dense_f * (1.5 if recompute else 1.0)
+    dense_tflops = dense_exec * args.steps / (dense_ms * 1e-3) / 1e12 if dense_ms > 0 else 0.0
     # HBM-bound block stages: algorithmic bytes = 2 s N d per apply (4 per projection side pair) ...
     es = 2 if cfg.dtype == "bf16" else 4
     unit = sum(es * N * (p["m"] + p["n"]) for p in projs)                 # one pass over an activation of each side
     ag_ms, ag_cnt = stages["apply_grad"]
     fused = ag_cnt > 0
     apply_bytes = (2 if fused else 4) * unit      # forward applies (+ backward applies when not fused): read + write
+    if recompute:
+        apply_bytes += 2 * sum(es * N * p["m"] for p in projs)            # A = R^T X once more
     bgrad_bytes = 2 * unit                        # separate block gradients: two reads per side
     ag_bytes = 3 * unit                           # one-pass backward block stage: read V, read U, write out
     apply_ms, _ = stages["apply"]
