@@ -38,6 +38,7 @@ constexpr int LPT = 2 * IPW;                     // loads per stage per wave
 constexpr int TM = 4, TN = 4;                    // 32 x 32 MFMA tiles of a wave
 constexpr int GROUP = 4;                         // tile rows walked together
 static_assert(NS * LPT < 64, "vmcnt range");
+static_assert(IPW == 4, "dma16g_s covers groups of four loads");
 
 struct DenseArgs {
   const uint16_t* A;     // A_KMAJOR: M x K row major (lda = K stride); else K x M
@@ -47,10 +48,23 @@ struct DenseArgs {
   int tiles_m, tiles_n, ktiles;   // ktiles counts 32-deep stages
 };
 
-// 16 bytes per lane from (uniform base + per-lane byte offset) straight into LDS at
-// lds_addr + 16 * lane.  Completion is tracked by hand through vmcnt.
-__device__ inline void dma16s(const void* sbase, uint32_t voff, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+// 16 bytes per lane from (uniform base + per-lane byte offset + OFF) straight into LDS at
+// lds_group + OFF + 16 * lane: the instruction offset moves the LDS address and the global address
+// alike, so the per-lane offsets of a group of loads are biased by -OFF and the whole group shares
+// one value of M0 (written once by the compiler, which tracks it as an operand).  Completion is
+// tracked by hand through vmcnt.
+template <int OFF>
+__device__ inline void dma16g(const void* sbase, uint32_t voff, uint32_t lds_group) {
+  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" ::"v"(voff), "s"(sbase), "n"(OFF), "{m0}"(lds_group) : "memory");
+}
+// load s of a wave's group of IPW = 4 (s is a constant wherever this is called)
+__device__ inline void dma16g_s(int s, const void* sbase, uint32_t voff, uint32_t lds_group) {
+  switch (s) {
+    case 0: dma16g<0>(sbase, voff, lds_group); break;
+    case 1: dma16g<1024>(sbase, voff, lds_group); break;
+    case 2: dma16g<2048>(sbase, voff, lds_group); break;
+    default: dma16g<3072>(sbase, voff, lds_group); break;
+  }
 }
 
 // DIAG (measurement builds only; the library instantiates DIAG = 0): bit 0 stops the direct-to-LDS loads
@@ -82,7 +96,9 @@ __global__ __launch_bounds__(256) void dense_stream_kernel(DenseArgs g) {
     j0 = ((u % per_group) / gsz) * BN;
   };
 
-  // per-lane byte offsets of the direct-to-LDS loads (the same for every stage and tile).
+  // per-lane byte offsets of the direct-to-LDS loads (the same for every stage and tile), less the
+  // instruction offset s * 1024 of load s (never negative: load s starts 16 s rows, or 2 s rows of at
+  // least 256 elements, into the tile).
   // Instruction (wave, s) fills LDS chunk slots [(wave*IPW + s)*64, +64) of the operand's part of
   // a stage; the lane's slot decides, through the inverse swizzle, which global chunk it fetches.
   uint32_t voffA[IPW], voffB[IPW];
@@ -91,13 +107,13 @@ __global__ __launch_bounds__(256) void dense_stream_kernel(DenseArgs g) {
     const int slot = (wave * IPW + s) * 64 + lane;
     if (A_KMAJOR) {
       const int r = slot >> 2, c = mm::xk_chunk(slot & 3, r);
-      voffA[s] = (uint32_t)((r * g.lda + c * 8) * 2);
+      voffA[s] = (uint32_t)((r * g.lda + c * 8) * 2) - s * 1024;
     } else {
       const int k = slot / (BM / 8), c = mm::kx_unchunk<BM>(slot % (BM / 8), k);
-      voffA[s] = (uint32_t)((k * g.lda + c * 8) * 2);
+      voffA[s] = (uint32_t)((k * g.lda + c * 8) * 2) - s * 1024;
     }
     const int k = slot / (BN / 8), c = mm::kx_unchunk<BN>(slot % (BN / 8), k);
-    voffB[s] = (uint32_t)((k * g.ldb + c * 8) * 2);
+    voffB[s] = (uint32_t)((k * g.ldb + c * 8) * 2) - s * 1024;
   }
   const i64 stepA = A_KMAJOR ? (i64)BK * 2 : (i64)BK * g.lda * 2;
   const i64 stepB = (i64)BK * g.ldb * 2;
@@ -116,8 +132,8 @@ __global__ __launch_bounds__(256) void dense_stream_kernel(DenseArgs g) {
   };
   issue_base(0);
   bool loads_on = true;   // DIAG bit 0 switches it off after the prologue
-  auto issue_a = [&](int s) { if (!(DIAG & 1) || loads_on) dma16s(Ab, voffA[s], lds_base + islot * STAGE_BYTES + (wave * IPW + s) * 1024); };
-  auto issue_b = [&](int s) { if (!(DIAG & 1) || loads_on) dma16s(Bb, voffB[s], lds_base + islot * STAGE_BYTES + A_BYTES + (wave * IPW + s) * 1024); };
+  auto issue_a = [&](int s) { if (!(DIAG & 1) || loads_on) dma16g_s(s, Ab, voffA[s], lds_base + islot * STAGE_BYTES + wave * IPW * 1024); };
+  auto issue_b = [&](int s) { if (!(DIAG & 1) || loads_on) dma16g_s(s, Bb, voffB[s], lds_base + islot * STAGE_BYTES + A_BYTES + wave * IPW * 1024); };
   // After the last stage of the last tile the stream keeps re-fetching that stage, so the number
   // of loads in flight -- and with it the vmcnt bound of the barrier -- never changes.
   auto issue_advance = [&]() {

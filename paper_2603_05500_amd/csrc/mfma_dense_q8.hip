@@ -47,11 +47,22 @@ struct DenseQ8Args {
   int tiles_m, tiles_n, ktiles;
 };
 
-__device__ inline void dma16s(const void* sbase, uint32_t voff, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+// Direct-to-LDS loads as in the bf16 kernel: the instruction offset moves the LDS and the global
+// address alike, so a group of loads shares one M0 and the per-lane offsets carry the bias.
+template <int OFF>
+__device__ inline void dma16g(const void* sbase, uint32_t voff, uint32_t lds_group) {
+  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" ::"v"(voff), "s"(sbase), "n"(OFF), "{m0}"(lds_group) : "memory");
+}
+__device__ inline void dma16g_s(int s, const void* sbase, uint32_t voff, uint32_t lds_group) {
+  switch (s) {
+    case 0: dma16g<0>(sbase, voff, lds_group); break;
+    case 1: dma16g<1024>(sbase, voff, lds_group); break;
+    case 2: dma16g<2048>(sbase, voff, lds_group); break;
+    default: dma16g<3072>(sbase, voff, lds_group); break;
+  }
 }
 __device__ inline void dma4s(const void* sbase, uint32_t voff, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+  asm volatile("global_load_lds_dword %0, %1" ::"v"(voff), "s"(sbase), "{m0}"(lds_addr) : "memory");
 }
 
 // A_KMAJOR: forward (weight rows are output rows, contraction along a row).  Otherwise backward
@@ -86,7 +97,7 @@ __global__ __launch_bounds__(256) void dense_q8_stream_kernel(DenseQ8Args g) {
   for (int s = 0; s < IPW; ++s) {
     const int slot = (wave * IPW + s) * 64 + lane;
     const int k = slot / (BN / 8), c = mm::kx_unchunk<BN>(slot % (BN / 8), k);
-    voffB[s] = (uint32_t)((k * g.ldb + c * 8) * 2);
+    voffB[s] = (uint32_t)((k * g.ldb + c * 8) * 2) - s * 1024;   // less the instruction offset of load s
   }
   const i64 stepB = (i64)BK * g.ldb * 2;
   const char* Bb;
@@ -97,7 +108,7 @@ __global__ __launch_bounds__(256) void dense_q8_stream_kernel(DenseQ8Args g) {
     Bb = (const char*)(g.B + j0);
   };
   b_base(0);
-  auto issue_b = [&](int s) { dma16s(Bb, voffB[s], lds_base + b_slot * STAGE_BYTES + A_BYTES + (wave * IPW + s) * 1024); };
+  auto issue_b = [&](int s) { dma16g_s(s, Bb, voffB[s], lds_base + b_slot * STAGE_BYTES + A_BYTES + wave * IPW * 1024); };
   auto b_advance = [&]() {
     b_slot = b_slot + 1 == NS ? 0 : b_slot + 1;
     if (b_kt + 1 < KT) { ++b_kt; Bb += stepB; }
@@ -118,13 +129,13 @@ __global__ __launch_bounds__(256) void dense_q8_stream_kernel(DenseQ8Args g) {
     const int ch = (wave * 2 + j) * 64 + lane;
     if (A_KMAJOR) {
       const int r = ch >> 1, c = ch & 1;
-      voffQ[j] = (uint32_t)(r * g.ldq + 16 * c);
+      voffQ[j] = (uint32_t)(r * g.ldq + 16 * c) - j * 1024;
       cvt_dst[j][0] = r * 64 + 16 * mm::xk_chunk(2 * c, r);
       cvt_dst[j][1] = r * 64 + 16 * mm::xk_chunk(2 * c + 1, r);
       cvt_scale[j] = Q_CODES + 4 * r;
     } else {
       const int k = ch >> 4, c = ch & 15;
-      voffQ[j] = (uint32_t)(k * g.ldq + 16 * c);
+      voffQ[j] = (uint32_t)(k * g.ldq + 16 * c) - j * 1024;
       cvt_dst[j][0] = k * (BM * 2) + 16 * mm::kx_chunk<BM>(2 * c, k);
       cvt_dst[j][1] = k * (BM * 2) + 16 * mm::kx_chunk<BM>(2 * c + 1, k);
       cvt_scale[j] = Q_CODES + 4 * (64 * wave + (k - 8 * wave));
@@ -144,8 +155,8 @@ __global__ __launch_bounds__(256) void dense_q8_stream_kernel(DenseQ8Args g) {
   q_base(0);
   auto issue_q = [&]() {
     const uint32_t slot = lds_base + Q_BASE + q_slot * Q_SLOT;
-    dma16s(Qb, voffQ[0], slot + (wave * 2 + 0) * 1024);
-    dma16s(Qb, voffQ[1], slot + (wave * 2 + 1) * 1024);
+    dma16g<0>(Qb, voffQ[0], slot + wave * 2 * 1024);
+    dma16g<1024>(Qb, voffQ[1], slot + wave * 2 * 1024);
     dma4s(Sb, voffS, slot + Q_CODES + wave * 256);
     q_slot = q_slot + 1 == NQ ? 0 : q_slot + 1;
     if (q_kt + 1 < KT) {
