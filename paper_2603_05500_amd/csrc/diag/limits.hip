@@ -126,7 +126,20 @@ static void time_dense(const char* what, const dense::DenseArgs& g, double flops
   auto kern = dense::dense_stream_kernel<A_KMAJOR, DIAG>;
   CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, dense::LDS_BYTES));
   const float ms = sustained_ms([&] { hipLaunchKernelGGL(kern, dim3(256), dim3(256), dense::LDS_BYTES, 0, g); }, 60, 40);
-  printf("  %-58s %.3f ms  %7.1f TFLOP/s\n", what, ms, flops / ms / 1e9);
+  // the same variant with the cycle counters in (DIAG bit 3): main loop and output of each workgroup's second tile
+  auto kclk = dense::dense_stream_kernel<A_KMAJOR, DIAG | 8>;
+  CHECK(hipFuncSetAttribute((const void*)kclk, hipFuncAttributeMaxDynamicSharedMemorySize, dense::LDS_BYTES));
+  for (int i = 0; i < 10; ++i) hipLaunchKernelGGL(kclk, dim3(256), dim3(256), dense::LDS_BYTES, 0, g);
+  CHECK(hipDeviceSynchronize());
+  static long long hc[2][1024];
+  CHECK(hipMemcpyFromSymbol(hc, HIP_SYMBOL(dense::g_diag_cycles), sizeof(hc)));
+  double loop = 0, outc = 0;
+  for (int i = 0; i < 1024; ++i) {
+    loop += (double)hc[0][i];
+    outc += (double)hc[1][i];
+  }
+  printf("  %-58s %.3f ms  %7.1f TFLOP/s   %6.0f cycles per 32-deep stage (32 MFMAs = 1024), %5.0f per tile output\n", what, ms, flops / ms / 1e9,
+         loop / 1024 / g.ktiles, outc / 1024);
 }
 
 int main() {
@@ -192,6 +205,7 @@ int main() {
     time_dense<false, 2>("backward, no fragment reads in the loop", g, flops);
     time_dense<false, 3>("backward, neither (MFMAs, barrier, epilogue only)", g, flops);
     time_dense<false, 4>("backward, every load re-fetches the first stage (cache hits)", g, flops);
+    time_dense<false, 6>("backward, cache-hit loads and no fragment reads", g, flops);
     // spot check of the unmodified kernel (forward)
     auto kern = dense::dense_stream_kernel<true, 0>;
     hipLaunchKernelGGL(kern, dim3(256), dim3(256), dense::LDS_BYTES, 0, g);

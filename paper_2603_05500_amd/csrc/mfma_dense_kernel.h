@@ -67,9 +67,13 @@ __device__ inline void dma16g_s(int s, const void* sbase, uint32_t voff, uint32_
   }
 }
 
+// DIAG bit 3: cycle counts of this workgroup's second tile, per wave: [0] its main loop, [1] its output.
+static __device__ long long g_diag_cycles[2][4 * 256];
+
 // DIAG (measurement builds only; the library instantiates DIAG = 0): bit 0 stops the direct-to-LDS loads
 // after the prologue, bit 1 stops the fragment reads inside the loop, bit 2 keeps the load addresses on
 // the first stage of the first tile (all loads hit in cache) -- the results are then wrong,
+// bit 3 (harmless to the result) records the cycle counts above --
 // every address stays what it was, and the timing shows what the loads or the reads cost.
 template <bool A_KMAJOR, int DIAG = 0>
 __global__ __launch_bounds__(256) void dense_stream_kernel(DenseArgs g) {
@@ -246,6 +250,8 @@ __global__ __launch_bounds__(256) void dense_stream_kernel(DenseArgs g) {
   auto run = [&](auto WC) {
     constexpr int W = decltype(WC)::value;
     for (int ti = 0; ti < n_my; ++ti) {
+      long long tc0 = 0, tc1 = 0;
+      if ((DIAG & 8) && ti == 1) tc0 = __builtin_readcyclecounter();
       for (int kt = 0; kt < KT; ++kt) {
         const char* stage = lds + cslot * STAGE_BYTES;
         // k step 0 from F; fetch k step 1 of this stage; B half of the stage in issue (its A half
@@ -275,6 +281,7 @@ __global__ __launch_bounds__(256) void dense_stream_kernel(DenseArgs g) {
         }
         cslot = nslot;
       }
+      if ((DIAG & 8) && ti == 1) tc1 = __builtin_readcyclecounter();
       // ---- tile done: round to bf16, swap register pairs between the lane halves so that a lane
       // holds 8 consecutive columns, store 16 bytes per lane, clear the accumulators
       int i0, j0;
@@ -302,6 +309,10 @@ __global__ __launch_bounds__(256) void dense_stream_kernel(DenseArgs g) {
             *reinterpret_cast<u32x4*>(Ct + (i64)a * 32 * g.ldc + c * 32 + 8 * q) = o;
           }
         }
+      if ((DIAG & 8) && ti == 1 && lane == 0 && blockIdx.x < 256) {
+        g_diag_cycles[0][blockIdx.x * 4 + W] = tc1 - tc0;
+        g_diag_cycles[1][blockIdx.x * 4 + W] = __builtin_readcyclecounter() - tc1;
+      }
     }
   };
   switch (wave) {
