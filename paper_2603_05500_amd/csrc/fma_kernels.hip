@@ -403,6 +403,10 @@ void fma_cnp_bwd(const float* theta, const float* dG, int d, int b, int k, float
 
 void skew_project_launch(const float* M, int b, int d, float* dtheta, int accumulate, hipStream_t st) {
   const int nb = ceil_div(d, b);
+  if (skew_tiled_supported(b, d)) {
+    skew_project_tiled_launch(M, b, nb, dtheta, accumulate, st);
+    return;
+  }
   const i64 total = (i64)nb * b * b;
   hipLaunchKernelGGL(skew_project_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, M, b, d, nb, dtheta,
                      accumulate);

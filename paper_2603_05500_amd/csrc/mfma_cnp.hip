@@ -123,6 +123,10 @@ void set_src(mm::Source& s, const uint16_t* A, const uint16_t* B, int b) {
 }  // namespace
 
 void skew_materialize_launch(const float* theta, int b, i64 nb, float* Qf, uint16_t* Qb, uint16_t* Tb, hipStream_t st) {
+  if (skew_tiled_supported(b, (i64)b)) {
+    skew_materialize_tiled_launch(theta, b, nb, Qf, Qb, Tb, st);
+    return;
+  }
   const i64 total = nb * b * b;
   hipLaunchKernelGGL(skew_materialize_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, theta, b, total, Qf, Qb, Tb);
 }
@@ -140,8 +144,7 @@ void mfma_cnp_build(const float* theta, int d, int b, int k, float* G_f32, void*
   float* Qf = ws;
   uint16_t* Qb = (uint16_t*)(Qf + total);
   uint16_t* H[2] = {Qb + total, Qb + 2 * total};
-  hipLaunchKernelGGL(skew_materialize_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, st, theta, b, total, Qf, Qb,
-                     (uint16_t*)nullptr);
+  skew_materialize_launch(theta, b, nb, Qf, Qb, nullptr, st);
   if (lds_cnp_supported(d, b)) {   // whole chain in one launch, block resident in LDS
     lds_cnp_build(Qf, Qb, d, k, G_f32, E_bf16, st);
     return;

@@ -84,6 +84,10 @@ const float* lds_cnp_bwd_chain(const uint16_t* Qb, const float* dG, int nb, int 
 // Q of nb blocks from packed parameters: Qf fp32 and/or Qb bf16, [nb][b][b] (either may be null).
 // Tb = bf16(-Q).
 void skew_materialize_launch(const float* theta, int b, i64 nb, float* Qf, uint16_t* Qb, uint16_t* Tb, hipStream_t st);
+// skew_tiled.hip: the same two operations through 64 x 64 tiles (coalesced on both sides of the transpose)
+bool skew_tiled_supported(int b, i64 d);
+void skew_materialize_tiled_launch(const float* theta, int b, i64 nb, float* Qf, uint16_t* Qb, uint16_t* Tb, hipStream_t st);
+void skew_project_tiled_launch(const float* M, int b, i64 nb, float* dtheta, int accumulate, hipStream_t st);
 // Series backward on the tiled kernels (b = 512) for nb blocks: Qf fp32, Tb = bf16(-Q); ws holds
 // 3.5 floats per block element; returns dL/dQ (inside ws).
 const float* mfma_cnp_bwd_chain(const float* Qf, const uint16_t* Tb, const float* dG, int nb, int b, int k, float* ws,
