@@ -150,7 +150,7 @@ __global__ __launch_bounds__(512) void apply_left_stream_kernel(const uint16_t* 
                                                                  uint16_t* __restrict__ out, i64 ld,
                                                                  const int32_t* __restrict__ perm,
                                                                  const uint16_t* __restrict__ blocks, int trans,
-                                                                 int tiles_per_wg) {
+                                                                 int tiles_per_wg, int paired_chunks) {
   constexpr int MSPLIT = B / 256, TN = BN / 32, KS = B / 16;
   constexpr int STAGE_BYTES = B * BN * 2;
   constexpr int CPR = BN / 8;                        // 16-byte chunks per row
@@ -159,9 +159,17 @@ __global__ __launch_bounds__(512) void apply_left_stream_kernel(const uint16_t* 
   extern __shared__ __attribute__((aligned(1024))) char ring[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int j = blockIdx.y;
-  const int slice = blockIdx.x % MSPLIT;
-  const i64 tok0 = (i64)(blockIdx.x / MSPLIT) * tiles_per_wg * BN;
+  // Which (block, slice, token range).  With two slices per block (paired_chunks > 0, one-dimensional
+  // grid) the two workgroups that read the same token tiles get ids 8 apart: consecutive ids go to the
+  // 8 XCDs in turn, so the pair shares one L2 and the tiles cross the fabric once.
+  int j = blockIdx.y, slice = blockIdx.x % MSPLIT, chunk = blockIdx.x / MSPLIT;
+  if (MSPLIT == 2 && paired_chunks > 0) {
+    const int id = blockIdx.x, pair = (id >> 4) * 8 + (id & 7);
+    slice = (id >> 3) & 1;
+    j = pair / paired_chunks;
+    chunk = pair % paired_chunks;
+  }
+  const i64 tok0 = (i64)chunk * tiles_per_wg * BN;
   const int32_t* pm = perm + (i64)j * B;
   const int li = lane & 31, h = lane >> 5;
   const uint32_t ring_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)ring;
@@ -336,7 +344,10 @@ void launch_apply_stream(const uint16_t* V, uint16_t* out, int d, i64 cols, i64 
   (void)configured;
   const int nb = d / B, tiles = (int)(cols / BN);
   const int chunks = stream_chunks(nb * MSPLIT, tiles);
-  hipLaunchKernelGGL(kern, dim3(chunks * MSPLIT, nb), dim3(512), LDS, st, V, out, ld, perm, E, trans, tiles / chunks);
+  if (MSPLIT == 2 && (nb * chunks) % 8 == 0)
+    hipLaunchKernelGGL(kern, dim3(chunks * MSPLIT * nb), dim3(512), LDS, st, V, out, ld, perm, E, trans, tiles / chunks, chunks);
+  else
+    hipLaunchKernelGGL(kern, dim3(chunks * MSPLIT, nb), dim3(512), LDS, st, V, out, ld, perm, E, trans, tiles / chunks, 0);
 }
 #ifndef SBN256_OVERRIDE
 #define SBN256_OVERRIDE 128
