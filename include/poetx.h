@@ -49,9 +49,11 @@
  *    whose pointers are not so aligned runs on the plain fp32-FMA kernels.
  *  - Which kernels serve a shape: the matrix-core kernels cover bf16 tensors with
  *    b = 256 or 512 dividing d_in and d_out, dimensions that are multiples of 256
- *    and token counts that are multiples of 256; everything else (fp32 tensors,
- *    small blocks, ragged tails) runs on plain fp32-FMA kernels, correct but one to
- *    two orders of magnitude slower at large sizes.  poetx_linear_path reports the
+ *    and token counts that are multiples of 256, and, for fp32 tensors, the two dense
+ *    products when all three dimensions are multiples of 128 (fp32 MFMA); everything
+ *    else (the structured stages and the series of fp32 tensors, small blocks, ragged
+ *    tails) runs on plain fp32-FMA kernels, correct but one to two orders of magnitude
+ *    slower at large sizes.  poetx_linear_path reports the
  *    choice for a descriptor, so a caller can refuse shapes that would fall off
  *    the fast path instead of finding out from the clock.
  *  - Output buffers must not overlap input buffers (in-place operation is refused:
@@ -270,7 +272,7 @@ size_t poetx_linear_workspace_bytes(const poetx_linear_desc* desc);
  * assumed).  Returns a combination of POETX_PATH_* bits, 0 when every stage runs on the plain
  * fp32-FMA kernels, or minus a poetx_status when the descriptor is invalid. */
 #define POETX_PATH_APPLY 1              /* gather + block-diagonal product + scatter            */
-#define POETX_PATH_DENSE 2              /* B = W A, dA = W^T dB                                */
+#define POETX_PATH_DENSE 2              /* B = W A, dA = W^T dB (the only bit fp32 tensors get) */
 #define POETX_PATH_BLOCKGRAD 4          /* block gradients (two-call backward)                 */
 #define POETX_PATH_SERIES 8             /* series backward on the matrix cores                 */
 #define POETX_PATH_SERIES_ON_CHIP 16    /* ... as one-launch chains with the block in LDS      */

@@ -90,6 +90,8 @@ void dense_dispatch(int dtype, int trans_w, const void* W, int n, int m, const v
   if (w_q8) mfma_dense_q8(trans_w, W, n, m, act, out, N, st);
   else if (use_mfma(dtype) && mfma_dense_supported(n, m, N) && aligned16(W) && aligned16(act) && aligned16(out))
     mfma_dense(trans_w, W, n, m, act, out, N, st);
+  else if (dtype == POETX_F32 && !g_force_fma.load() && mfma_dense_f32_supported(n, m, N) && aligned16(W) && aligned16(act) && aligned16(out))
+    mfma_dense_f32(trans_w, W, n, m, act, out, N, st);
   else fma_dense(dtype, trans_w, W, n, m, act, out, N, st);
 }
 
@@ -292,6 +294,7 @@ int poetx_linear_path(const poetx_linear_desc* d) {
   const int m = d->d_in, n = d->d_out, b = d->block;
   const i64 N = d->n_tokens;
   int path = 0;
+  if (d->dtype == POETX_F32 && !g_force_fma.load() && mfma_dense_f32_supported(n, m, N)) path |= POETX_PATH_DENSE;   // fp32 MFMA; the other stages of fp32 tensors stay on the plain-FMA kernels
   if (!use_mfma(d->dtype)) return path;
   if (mfma_apply_left_supported(m, N, N, b) && mfma_apply_left_supported(n, N, N, b)) path |= POETX_PATH_APPLY;
   if (mfma_dense_supported(n, m, N)) path |= POETX_PATH_DENSE;

@@ -52,6 +52,9 @@ void perm_validate_launch(const int32_t* perm, int d, int32_t* scratch, hipStrea
 bool mfma_dense_supported(int n, int m, i64 N);
 void mfma_dense(int trans_w, const void* W, int n, int m, const void* act, void* out, i64 N,
                 hipStream_t st);
+// the same products for fp32 tensors (fp32 MFMA, mfma_dense_f32.hip)
+bool mfma_dense_f32_supported(int n, int m, i64 N);
+void mfma_dense_f32(int trans_w, const void* W, int n, int m, const void* act, void* out, i64 N, hipStream_t st);
 // the same products on a quantised weight buffer (codes + row scales), dequantised inside the kernel (mfma_dense_q8.hip)
 bool mfma_dense_q8_supported(int n, int m, i64 N);
 void mfma_dense_q8(int trans_w, const void* Wq, int n, int m, const void* act, void* out, i64 N, hipStream_t st);

@@ -101,12 +101,14 @@ def test_flag_and_quantised_weight_checks(clib):
 
 def test_linear_path_query(clib):
     """poetx_linear_path tells which stages the matrix-core kernels serve: all of them for the benchmark
-    shapes, none for fp32 tensors or small blocks, and the INT8 bit only with the flag."""
+    shapes, the dense products alone for fp32 tensors, none for small shapes, and the INT8 bit only with the flag."""
     full = px.PATH_APPLY | px.PATH_DENSE | px.PATH_BLOCKGRAD | px.PATH_SERIES | px.PATH_SERIES_ON_CHIP | px.PATH_BWD_ONE_PASS
     assert px.poetx_linear_path(px.make_desc(4096, 14336, 256, 5, 16384, px.BF16)) == full
     b512 = px.poetx_linear_path(px.make_desc(4096, 1024, 512, 5, 16384, px.BF16))
     assert b512 == px.PATH_APPLY | px.PATH_DENSE | px.PATH_BLOCKGRAD | px.PATH_SERIES
-    assert px.poetx_linear_path(px.make_desc(256, 256, 32, 4, 512, px.F32)) == 0
+    # fp32 tensors: only the dense products have a matrix-core kernel (fp32 MFMA), for multiples of 128
+    assert px.poetx_linear_path(px.make_desc(256, 256, 32, 4, 512, px.F32)) == px.PATH_DENSE
+    assert px.poetx_linear_path(px.make_desc(64, 64, 16, 3, 256, px.F32)) == 0
     assert px.poetx_linear_path(px.make_desc(512, 1376, 64, 4, 1024, px.BF16)) == 0
     xq = px.make_desc(4096, 4096, 256, 5, 16384, px.BF16, flags=px.FLAG_RECOMPUTE_B | px.FLAG_W_INT8)
     assert px.poetx_linear_path(xq) == full | px.PATH_W_INT8_IN_KERNEL

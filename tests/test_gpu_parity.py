@@ -300,6 +300,25 @@ def test_plain_series_orders(lib, k, b, dtype):
     check_layer(res, ref, data["pi_P"], dtype)
 
 
+@pytest.mark.parametrize("m,n,N,b,k", [(256, 384, 256, 64, 4), (640, 128, 384, 128, 3), (128, 128, 128, 32, 5)])
+def test_fp32_layer_dense_on_matrix_cores(lib, m, n, N, b, k):
+    """fp32 tensors whose dense products fit the fp32 matrix-core kernel (multiples of 128): the layer
+    against the oracle at the fp32 tolerance, and the same inputs through the plain-FMA kernels."""
+    data = synth_layer(7600 + m + n + N + b, m, n, N, b, k, "f32", 0.01)
+    ref = orc.linear_fwd_bwd_from_theta(data["X"], data["dZ"], data["W"], data["pi_R"], data["pi_P"],
+                                        data["theta_R"], data["theta_P"], b, k)
+    desc = lib.make_desc(m, n, b, k, N, lib.F32)
+    assert lib.poetx_linear_path(desc) & lib.PATH_DENSE
+    check_layer(run_layer(data, "f32"), ref, data["pi_P"], "f32")
+    lib.poetx_debug_force_fma(True)
+    try:
+        assert not (lib.poetx_linear_path(desc) & lib.PATH_DENSE)
+        res2 = run_layer(data, "f32")
+    finally:
+        lib.poetx_debug_force_fma(False)
+    check_layer(res2, ref, data["pi_P"], "f32")
+
+
 @pytest.mark.parametrize("N", [64, 128, 192, 320, 384, 576])
 def test_kernel_family_boundaries(lib, N):
     """Token counts around the tile sizes of the matrix-core kernels (128-token apply tiles, 256-token
