@@ -251,13 +251,28 @@ __global__ __launch_bounds__(512) void apply_grad_stream_kernel(GradArgs g) {
       }
       slot = slot + 1 == G_NS ? 0 : slot + 1;
     }
-    float* P = g.partial + (((i64)chunk * g.nb + j) * GB + half * 128 + gw * 32 + li) * GB + 4 * h;
+    // A lane holds columns 8q + 4h .. + 3 of its row for q = 0..3.  Swapping register groups between the lane
+    // halves (v_permlane32_swap: the upper half of its first operand against the lower half of its second)
+    // leaves the lower lanes with columns 8q .. 8q + 7 and the upper lanes with 8(q+1) .. 8(q+1) + 7:
+    // every lane stores whole 32-byte sectors.
+    typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+    float* P = g.partial + (((i64)chunk * g.nb + j) * GB + half * 128 + gw * 32 + li) * GB + 8 * h;
 #pragma unroll
     for (int ct = 0; ct < 8; ++ct)
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        *reinterpret_cast<float4*>(P + ct * 32 + 8 * q) =
-            make_float4(acc[ct][4 * q], acc[ct][4 * q + 1], acc[ct][4 * q + 2], acc[ct][4 * q + 3]);
+      for (int q = 0; q < 4; q += 2) {
+        float lo[4], hi[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float x = acc[ct][4 * q + e], y = acc[ct][4 * q + 4 + e];   // scalars first: a bit cast straight from a vector element reads element 0
+          const uint2v r = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, y), false, false);
+          const unsigned r0 = r[0], r1 = r[1];
+          lo[e] = __builtin_bit_cast(float, r0);
+          hi[e] = __builtin_bit_cast(float, r1);
+        }
+        *reinterpret_cast<float4*>(P + ct * 32 + 8 * q) = make_float4(lo[0], lo[1], lo[2], lo[3]);
+        *reinterpret_cast<float4*>(P + ct * 32 + 8 * q + 4) = make_float4(hi[0], hi[1], hi[2], hi[3]);
+      }
   }
 }
 

@@ -91,11 +91,23 @@ __global__ __launch_bounds__(256) void cnp_chain_kernel(ChainArgs a) {
     constexpr int NCH = LB * LB / 8 / 256;   // chunks per thread
     const u32x4* src = reinterpret_cast<const u32x4*>(a.Qb + blk);
     u32x4 v[NCH];
-#pragma unroll
-    for (int it = 0; it < NCH; ++it) v[it] = src[tid + 256 * it];
+    // Chunk (row, kc) of a wave's two rows goes to lane 16 * (2 * (kc >> 4) + (row & 1)) + (kc & 15): the 8-byte
+    // writes of a half wave then cover rows 2p and 2p + 1 (4 banks apart) over 16 chunks each = all 64 banks once.
+    auto chunk_of = [&](int id, int& row, int& kc) {
+      const int l = id & 63;
+      row = 2 * (id >> 6) + ((l >> 4) & 1);
+      kc = (l & 15) + 16 * (l >> 5);
+    };
 #pragma unroll
     for (int it = 0; it < NCH; ++it) {
-      const int id = tid + 256 * it, row = id >> 5, kc = id & 31;
+      int row, kc;
+      chunk_of(tid + 256 * it, row, kc);
+      v[it] = src[row * 32 + kc];
+    }
+#pragma unroll
+    for (int it = 0; it < NCH; ++it) {
+      int row, kc;
+      chunk_of(tid + 256 * it, row, kc);
       char* dst = lds + row * LROW + 32 * (kc >> 1) + 8 * (kc & 1);
       *reinterpret_cast<uint2*>(dst) = make_uint2(v[it][0], v[it][1]);
       *reinterpret_cast<uint2*>(dst + 16) = make_uint2(v[it][2], v[it][3]);
