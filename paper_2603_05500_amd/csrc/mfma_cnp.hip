@@ -110,11 +110,20 @@ struct EpiBwdStep {
   }
 };
 
+// 512-wide blocks take 256 x 256 output tiles (8 waves of 128 x 64): four times the work per
+// workgroup for the same 512-deep contraction, whose fill and drain dominate a 128 x 128 tile.
+inline bool big_tiles(int b) { return b % 256 == 0 && b >= 512; }
 mm::Args batched_args(int b) {
   mm::Args g{};
-  g.tiles_m = b / CBM;
-  g.tiles_n = b / CBN;
+  const int t = big_tiles(b) ? 256 : CBM;
+  g.tiles_m = b / t;
+  g.tiles_n = b / t;
   return g;
+}
+template <class Epi>
+void launch_product(int b, const mm::Args& g, Epi epi, int batches, hipStream_t st) {
+  if (big_tiles(b)) mm::launch<256, 256, 2, 4, true, false, false, CNS, true>(g, epi, batches, 1, st);
+  else mm::launch<CBM, CBN, 2, 2, true, false, false, CNS, true>(g, epi, batches, 1, st);
 }
 void set_src(mm::Source& s, const uint16_t* A, const uint16_t* B, int b) {
   s.A = A; s.B = B; s.lda = b; s.ldb = b; s.sA = (i64)b * b; s.sB = (i64)b * b; s.ktiles = b / CBK;
@@ -157,7 +166,7 @@ void mfma_cnp_build(const float* theta, int d, int b, int k, float* G_f32, void*
     set_src(g.s[0], cur, Qb, b);
     uint16_t* nxt = H[step & 1];
     EpiHorner epi{Qf, 2.f, b, last ? nullptr : nxt, last ? G_f32 : nullptr, last ? (uint16_t*)E_bf16 : nullptr};
-    mm::launch<CBM, CBN, 2, 2, true, false, false, CNS, true>(g, epi, nb, 1, st);
+    launch_product(b, g, epi, nb, st);
     cur = nxt;
   }
 }
@@ -206,7 +215,7 @@ const float* mfma_cnp_bwd_chain(const float* Qf, const uint16_t* Tb, const float
       set_src(g.alt[0], acur, Tb, b);
     }
     EpiBwdStep epi{dG, Qf, b, nb, last ? nullptr : Bb[ib], last ? Bfinal : nullptr, last ? nullptr : A[ia]};
-    mm::launch<CBM, CBN, 2, 2, true, false, false, CNS, true>(g, epi, last ? nb : 2 * nb, 1, st);
+    launch_product(b, g, epi, last ? nb : 2 * nb, st);
     if (!last) {
       acur = A[ia];
       ia ^= 1;
