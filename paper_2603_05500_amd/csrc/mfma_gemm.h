@@ -90,6 +90,10 @@ struct Args {
   int tiles_m, tiles_n;      // output tiles per batch
   const int32_t* perm;       // GATHER: row r of batch j of both operands is memory row perm[j*rows_per_batch + r]
   int rows_per_batch;
+  // Set by launch(): > 0 means a one-dimensional grid in which the tiles of one (batch, split) get
+  // workgroup ids 8 apart, i.e. run on one XCD at the same time and share their operand panels in its
+  // L2 (consecutive ids go to the 8 XCDs in turn); the value is the number of batches.
+  int xcd_batches;
 };
 
 // NS = ring depth (stages); up to NS - 1 tiles are in flight while one is multiplied.
@@ -163,14 +167,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(Args g, Epi e
   // of 4 tile rows.
   int wg = blockIdx.x;
   const int total = g.tiles_m * g.tiles_n;
-  if ((total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);
+  int batch = blockIdx.y, split = blockIdx.z;
+  if (g.xcd_batches > 0) {
+    const int slot = blockIdx.x >> 3, work = (slot / total) * 8 + (blockIdx.x & 7);
+    wg = slot % total;
+    batch = work % g.xcd_batches;
+    split = work / g.xcd_batches;
+  } else if ((total & 7) == 0) wg = (wg & 7) * (total >> 3) + (wg >> 3);
   constexpr int GROUP = 4;
   const int per_group = GROUP * g.tiles_n;
   const int first_m = (wg / per_group) * GROUP;
   const int gsz = (g.tiles_m - first_m) < GROUP ? (g.tiles_m - first_m) : GROUP;
   const int tile_m = first_m + (wg % per_group) % gsz;
   const int tile_n = (wg % per_group) / gsz;
-  const int batch = blockIdx.y, split = blockIdx.z;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -375,6 +384,14 @@ void launch(const Args& g, Epi epi, int batches, int splits, hipStream_t st) {
   static const bool configured =
       hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES) == hipSuccess;
   (void)configured;
+  // a few tiles per (batch, split) that read the same operand rows: keep them on one XCD
+  const int tiles = g.tiles_m * g.tiles_n;
+  if (tiles > 1 && tiles <= 16 && ((i64)batches * splits) % 8 == 0) {
+    Args h = g;
+    h.xcd_batches = batches;
+    hipLaunchKernelGGL(kern, dim3(tiles * batches * splits), dim3(64 * WGM * WGN), C::LDS_BYTES, st, h, epi);
+    return;
+  }
   hipLaunchKernelGGL(kern, dim3(g.tiles_m * g.tiles_n, batches, splits), dim3(64 * WGM * WGN), C::LDS_BYTES, st, g, epi);
 }
 
