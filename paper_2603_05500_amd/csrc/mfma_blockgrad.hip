@@ -19,6 +19,11 @@ struct EpiPartial {
   __device__ void operator()(int batch, int split, int row, int col, float4 v) const {
     *reinterpret_cast<float4*>(out + split * split_stride + ((i64)batch * b + row) * b + col) = v;
   }
+  __device__ void wide(int batch, int split, int row, int col, float4 lo, float4 hi) const {   // whole 32-byte sectors
+    float* p = out + split * split_stride + ((i64)batch * b + row) * b + col;
+    *reinterpret_cast<float4*>(p) = lo;
+    *reinterpret_cast<float4*>(p + 4) = hi;
+  }
 };
 
 __global__ void reduce_partials_kernel(const float4* __restrict__ part, float4* __restrict__ out, i64 n4, int splits) {

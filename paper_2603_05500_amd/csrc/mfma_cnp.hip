@@ -80,6 +80,28 @@ struct EpiHorner {
       for (int e = 0; e < 4; ++e) E[base + (i64)b * b + (i64)(col + e) * b + row] = float_to_bf16_bits(v[e]);
     }
   }
+  // eight consecutive columns: 32-byte reads of Q, 16-byte stores of the bf16 outputs
+  __device__ void wide(int j, int, int row, int col, float4 lo, float4 hi) const {
+    const i64 o = ((i64)j * b + row) * b + col;
+    const float4 q0 = *reinterpret_cast<const float4*>(Qf + o), q1 = *reinterpret_cast<const float4*>(Qf + o + 4);
+    const float v[8] = {lo.x + coef * q0.x, lo.y + coef * q0.y, lo.z + coef * q0.z, lo.w + coef * q0.w,
+                        hi.x + coef * q1.x, hi.y + coef * q1.y, hi.z + coef * q1.z, hi.w + coef * q1.w};
+    const uint4 pk = make_uint4(mm::pack2_bf16(v[0], v[1]), mm::pack2_bf16(v[2], v[3]), mm::pack2_bf16(v[4], v[5]), mm::pack2_bf16(v[6], v[7]));
+    if (Hn) *reinterpret_cast<uint4*>(Hn + o) = pk;
+    if (G) {
+      float gv[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) gv[e] = v[e] + (row == col + e ? 1.f : 0.f);
+      *reinterpret_cast<float4*>(G + o) = make_float4(gv[0], gv[1], gv[2], gv[3]);
+      *reinterpret_cast<float4*>(G + o + 4) = make_float4(gv[4], gv[5], gv[6], gv[7]);
+    }
+    if (E) {
+      const i64 base = (i64)j * 2 * b * b;
+      *reinterpret_cast<uint4*>(E + base + (i64)row * b + col) = pk;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) E[base + (i64)b * b + (i64)(col + e) * b + row] = float_to_bf16_bits(v[e]);
+    }
+  }
 };
 
 // One backward step in one launch.  Batches [0, nb): Bm_next = acc + 2 D  (bf16 chain value and/or
@@ -106,6 +128,26 @@ struct EpiBwdStep {
     } else {
       if (Bn) *reinterpret_cast<uint2*>(Bn + o) = pk;
       if (Bf) *reinterpret_cast<float4*>(Bf + o) = v;
+    }
+  }
+  __device__ void wide(int batch, int, int row, int col, float4 lo, float4 hi) const {
+    const bool second = batch >= nb;
+    const int j = second ? batch - nb : batch;
+    const i64 o = ((i64)j * b + row) * b + col;
+    const float* src = (second ? Qf : D) + o;
+    const float4 d0 = *reinterpret_cast<const float4*>(src), d1 = *reinterpret_cast<const float4*>(src + 4);
+    const float coef = second ? -2.f : 2.f;
+    const float4 v0 = make_float4(lo.x + coef * d0.x, lo.y + coef * d0.y, lo.z + coef * d0.z, lo.w + coef * d0.w);
+    const float4 v1 = make_float4(hi.x + coef * d1.x, hi.y + coef * d1.y, hi.z + coef * d1.z, hi.w + coef * d1.w);
+    const uint4 pk = make_uint4(mm::pack2_bf16(v0.x, v0.y), mm::pack2_bf16(v0.z, v0.w), mm::pack2_bf16(v1.x, v1.y), mm::pack2_bf16(v1.z, v1.w));
+    if (second) {
+      *reinterpret_cast<uint4*>(An + o) = pk;
+    } else {
+      if (Bn) *reinterpret_cast<uint4*>(Bn + o) = pk;
+      if (Bf) {
+        *reinterpret_cast<float4*>(Bf + o) = v0;
+        *reinterpret_cast<float4*>(Bf + o + 4) = v1;
+      }
     }
   }
 };

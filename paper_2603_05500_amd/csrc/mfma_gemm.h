@@ -23,6 +23,7 @@
 // transposed: a lane owns one output row and four consecutive columns, handed to
 // the epilogue as one float4.
 #pragma once
+#include <type_traits>
 
 #include "poetx_kernels.h"
 
@@ -144,6 +145,13 @@ __device__ inline void wait_tiles_and_barrier(int tiles) {
     else wait_tiles_and_barrier<LPT, MAXT - 1>(tiles);
   }
 }
+
+// An epilogue may also offer  void wide(int batch, int split, int row, int col, float4 lo, float4 hi)  for
+// eight consecutive columns col..col+7; the kernel then calls that instead (wider loads and stores).
+template <class E, class = void>
+struct has_wide : std::false_type {};
+template <class E>
+struct has_wide<E, std::void_t<decltype(&E::wide)>> : std::true_type {};
 
 // Epi: __device__ void operator()(int batch, int split, int row, int col, float4 v) -- four
 // consecutive columns col..col+3 of output row `row` (indices local to the batch).
@@ -361,16 +369,44 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(Args g, Epi e
   wait_vmcnt_and_barrier<0>();
 
   const int h = lane >> 5, li = lane & 31;
+  if constexpr (has_wide<Epi>::value) {
+    // An epilogue that takes 8 consecutive columns: register groups q and q + 1 are swapped between the
+    // lane halves (v_permlane32_swap: the upper half of its first operand against the lower half of its
+    // second), after which the lower lanes hold columns 8q .. 8q + 7 and the upper lanes 8(q+1) .. + 7.
+    typedef unsigned uint2v __attribute__((ext_vector_type(2)));
 #pragma unroll
-  for (int a = 0; a < TM; ++a) {
-    const int row = i0 + wm * (BM / WGM) + a * 32 + li;
+    for (int a = 0; a < TM; ++a) {
+      const int row = i0 + wm * (BM / WGM) + a * 32 + li;
 #pragma unroll
-    for (int c = 0; c < TN; ++c) {
-      const int col = j0 + wn * (BN / WGN) + c * 32 + 4 * h;
+      for (int c = 0; c < TN; ++c) {
+        const int col = j0 + wn * (BN / WGN) + c * 32 + 8 * h;
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        epi(batch, split, row, col + 8 * q,
-            make_float4(acc[a][c][4 * q], acc[a][c][4 * q + 1], acc[a][c][4 * q + 2], acc[a][c][4 * q + 3]));
+        for (int q = 0; q < 4; q += 2) {
+          float lo[4], hi[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float x = acc[a][c][4 * q + e], y = acc[a][c][4 * q + 4 + e];   // scalars first: a bit cast straight from a vector element reads element 0
+            const uint2v r = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, y), false, false);
+            const unsigned r0 = r[0], r1 = r[1];
+            lo[e] = __builtin_bit_cast(float, r0);
+            hi[e] = __builtin_bit_cast(float, r1);
+          }
+          epi.wide(batch, split, row, col + 8 * q, make_float4(lo[0], lo[1], lo[2], lo[3]), make_float4(hi[0], hi[1], hi[2], hi[3]));
+        }
+      }
+    }
+  } else {
+#pragma unroll
+    for (int a = 0; a < TM; ++a) {
+      const int row = i0 + wm * (BM / WGM) + a * 32 + li;
+#pragma unroll
+      for (int c = 0; c < TN; ++c) {
+        const int col = j0 + wn * (BN / WGN) + c * 32 + 4 * h;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          epi(batch, split, row, col + 8 * q,
+              make_float4(acc[a][c][4 * q], acc[a][c][4 * q + 1], acc[a][c][4 * q + 2], acc[a][c][4 * q + 3]));
+      }
     }
   }
 }
