@@ -289,15 +289,20 @@ __global__ void reduce_grad_partials_kernel(const float4* __restrict__ part, flo
 
 // token ranges per block: workgroups = 2 nb chunks; fill the CUs in whole rounds, keep at least
 // 4 tiles per workgroup (the two tiles of lead-in are then a small share)
+// Token chunks per half block.  More chunks fill the 256 CUs in whole rounds, but every chunk writes an
+// fp32 partial of its half block that the reduction reads again: the choice minimises the bytes moved,
+// with the three activation passes weighted by the share of the CUs that the workgroups keep busy.
 int grad_chunks(int nb, int tiles) {
   int best = 1;
-  double best_eff = 0.0;
+  double best_cost = 0.0;
+  const double act = 3.0 * nb * GB * (double)tiles * GBN * 2.0;
   for (int c = 1; c <= tiles; c *= 2) {
     if (tiles % c != 0 || tiles / c < 4) break;
     const double wgs = 2.0 * nb * c;
     const double rounds = (double)(long long)((wgs + 255) / 256);
     const double eff = wgs / 256.0 / rounds;
-    if (eff > best_eff + 1e-9) { best_eff = eff; best = c; }
+    const double cost = act / eff + (c > 1 ? 2.0 * c * nb * GB * GB * 4.0 : 0.0);
+    if (c == 1 || cost < best_cost) { best_cost = cost; best = c; }
   }
   return best;
 }
