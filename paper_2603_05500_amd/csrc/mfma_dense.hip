@@ -8,8 +8,8 @@
 // The kernel is a persistent stream: one workgroup per CU, 4 waves (2 x 2, one per SIMD), each
 // wave owning a 128 x 128 piece of a 256 x 256 output tile in 256 accumulator registers
 // (v_mfma_f32_32x32x16_bf16, fp32).  A workgroup walks its list of output tiles; the 32-deep
-// operand stages of ALL its tiles form one stream that flows through a ring of NS LDS stages,
-// filled by direct-to-LDS loads issued NS stages ahead of the multiplication -- across tile
+// operand stages of ALL its tiles form one stream that flows through a ring of 4 LDS stages,
+// filled by direct-to-LDS loads issued that many stages ahead of the multiplication -- across tile
 // boundaries, so a new tile starts multiplying the moment the previous one is rounded and stored.
 // Per stage there is one barrier, placed after the first of the two k steps, where every wave
 // holds the rest of the stage in registers: the stage's slot is refilled at once.  Loads and

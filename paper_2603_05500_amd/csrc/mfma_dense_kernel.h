@@ -8,8 +8,9 @@
 // The kernel is a persistent stream: one workgroup per CU, 4 waves (2 x 2, one per SIMD), each
 // wave owning a 128 x 128 piece of a 256 x 256 output tile in 256 accumulator registers
 // (v_mfma_f32_32x32x16_bf16, fp32).  A workgroup walks its list of output tiles; the 32-deep
-// operand stages of ALL its tiles form one stream that flows through a ring of NS LDS stages,
-// filled by direct-to-LDS loads issued NS stages ahead of the multiplication -- across tile
+// operand stages of ALL its tiles form one stream that flows through a ring of 4 LDS stages
+// (a fifth buys nothing measurable; its 32 KB stage the output instead),
+// filled by direct-to-LDS loads issued that many stages ahead of the multiplication -- across tile
 // boundaries, so a new tile starts multiplying the moment the previous one is rounded and stored.
 // Per stage there is one barrier, placed after the first of the two k steps, where every wave
 // holds the rest of the stage in registers: the stage's slot is refilled at once.  Loads and
@@ -30,9 +31,10 @@ using mm::floatx16;
 using mm::short4v;
 using mm::short8v;
 
-constexpr int BM = 256, BN = 256, BK = 32, NW = 4, NS = 5;
+constexpr int BM = 256, BN = 256, BK = 32, NW = 4, NS = 4;
 constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
-constexpr int LDS_BYTES = NS * STAGE_BYTES;      // 160 KB: the whole LDS of a CU
+constexpr int OUT_BYTES = 8192;                  // per-wave output staging: two 32-row x 64-column pieces
+constexpr int LDS_BYTES = NS * STAGE_BYTES + NW * OUT_BYTES;   // 128 + 32 = 160 KB: the whole LDS of a CU
 constexpr int IPW = A_BYTES / 1024 / NW;         // direct-to-LDS instructions per wave per operand per stage
 constexpr int LPT = 2 * IPW;                     // loads per stage per wave
 constexpr int TM = 4, TN = 4;                    // 32 x 32 MFMA tiles of a wave
@@ -241,9 +243,7 @@ __global__ __launch_bounds__(256) void dense_stream_kernel(DenseArgs g) {
     for (int p = 0; p < 8; ++p) load_piece(Gf, lds, 1, p);
   }
   loads_on = false;
-  // output: after the half swap a lane owns row wm*128 + a*32 + li and 8 consecutive columns
   const int h = lane >> 5, li = lane & 31;
-  const i64 coff = (i64)(wm * (BM / 2) + li) * g.ldc + wn * (BN / 2) + 8 * h;
 
   // The body is instantiated once per wave: wave W issues its four loads of a k step after MFMAs
   // W, W+4, W+8 and W+12, so the four waves never hand the memory pipeline a load in the same place.
@@ -282,33 +282,51 @@ __global__ __launch_bounds__(256) void dense_stream_kernel(DenseArgs g) {
         cslot = nslot;
       }
       if ((DIAG & 8) && ti == 1) tc1 = __builtin_readcyclecounter();
-      // ---- tile done: round to bf16, swap register pairs between the lane halves so that a lane
-      // holds 8 consecutive columns, store 16 bytes per lane, clear the accumulators
-      int i0, j0;
-      tile_origin(ti, i0, j0);
-      uint16_t* Ct = g.C + (i64)i0 * g.ldc + j0 + coff;
+      // ---- tile done: round to bf16 and store, clear the accumulators.  The accumulator layout gives a
+      // lane 4 consecutive columns of its row per register group; swapping groups between the lane halves
+      // (v_permlane32_swap: the upper half of its first operand against the lower half of its second)
+      // makes that 8 columns = 16 bytes.  Stored like this an instruction would write 32 contiguous bytes
+      // per row, and all workgroups finish their tiles together: the burst drains twice as fast when
+      // every instruction writes whole 128-byte lines.  So the wave passes its piece through LDS, 32 rows
+      // x 64 columns at a time (rows XOR-swizzled in 16-byte chunks, conflict free both ways), and reads
+      // it back with 8 lanes per row.
+      {
+        typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        int i0, j0;
+        tile_origin(ti, i0, j0);
+        char* stg = lds + NS * STAGE_BYTES + wave * OUT_BYTES;
+        const int wsw = (li >> 1) & 7;
+        uint16_t* Cw = g.C + (i64)(i0 + wm * (BM / 2)) * g.ldc + j0 + wn * (BN / 2);
 #pragma unroll
-      for (int a = 0; a < TM; ++a)
+        for (int a = 0; a < TM; ++a) {
 #pragma unroll
-        for (int c = 0; c < TN; ++c) {
-          uint32_t p[8];   // p[2q], p[2q+1]: columns 8q + 4h + 0..3 of the 32-column tile
+          for (int c = 0; c < TN; ++c) {
+            uint32_t p[8];   // p[2q], p[2q+1]: columns 8q + 4h + 0..3 of the 32-column tile
 #pragma unroll
-          for (int e = 0; e < 8; ++e) p[e] = mm::pack2_bf16(acc[a][c][2 * e], acc[a][c][2 * e + 1]);
+            for (int e = 0; e < 8; ++e) p[e] = mm::pack2_bf16(acc[a][c][2 * e], acc[a][c][2 * e + 1]);
 #pragma unroll
-          for (int v = 0; v < 16; ++v) acc[a][c][v] = 0.f;
+            for (int v = 0; v < 16; ++v) acc[a][c][v] = 0.f;
 #pragma unroll
-          for (int q = 0; q < 4; q += 2) {
-            // v_permlane32_swap exchanges the upper lane half of its first operand with the lower
-            // half of its second: lower lanes end up with columns 8q .. 8q+7, upper lanes with
-            // columns 8(q+1) .. 8(q+1)+7 of their row
-            typedef unsigned uint2v __attribute__((ext_vector_type(2)));
-            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-            const uint2v r0 = __builtin_amdgcn_permlane32_swap(p[2 * q], p[2 * q + 2], false, false);
-            const uint2v r1 = __builtin_amdgcn_permlane32_swap(p[2 * q + 1], p[2 * q + 3], false, false);
-            const u32x4 o = {r0[0], r1[0], r0[1], r1[1]};
-            *reinterpret_cast<u32x4*>(Ct + (i64)a * 32 * g.ldc + c * 32 + 8 * q) = o;
+            for (int q = 0; q < 4; q += 2) {
+              const uint2v r0 = __builtin_amdgcn_permlane32_swap(p[2 * q], p[2 * q + 2], false, false);
+              const uint2v r1 = __builtin_amdgcn_permlane32_swap(p[2 * q + 1], p[2 * q + 3], false, false);
+              const u32x4 o = {r0[0], r1[0], r0[1], r1[1]};   // columns 8 (q + h) .. + 7 of tile c
+              const int ch = (c & 1) * 4 + q + h;             // 16-byte chunk of the 64-column piece
+              *reinterpret_cast<u32x4*>(stg + (c >> 1) * 4096 + li * 128 + 16 * (ch ^ wsw)) = o;
+            }
           }
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's own writes; the area is private to it
+#pragma unroll
+          for (int cp = 0; cp < 2; ++cp)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const int r = (lane >> 3) + 8 * i, ch = lane & 7;
+              const u32x4 o = *reinterpret_cast<const u32x4*>(stg + cp * 4096 + r * 128 + 16 * (ch ^ ((r >> 1) & 7)));
+              *reinterpret_cast<u32x4*>(Cw + (i64)(a * 32 + r) * g.ldc + cp * 64 + ch * 8) = o;
+            }
         }
+      }
       if ((DIAG & 8) && ti == 1 && lane == 0 && blockIdx.x < 256) {
         g_diag_cycles[0][blockIdx.x * 4 + W] = tc1 - tc0;
         g_diag_cycles[1][blockIdx.x * 4 + W] = __builtin_readcyclecounter() - tc1;
