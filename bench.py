@@ -22,7 +22,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 # L2<->fabric bytes per dense launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by
 # what the same counters read for a 1 GiB copy (2.0 and 1.0); see profiles/llama8b_b256_layer_counters.md.
-DENSE_TRAFFIC_BYTES_PER_LAUNCH = {"llama8b-b256": 1.72e9}
+DENSE_TRAFFIC_BYTES_PER_LAUNCH = {"llama8b-b256": 1.81e9}
 
 
 def parse():
