@@ -131,15 +131,25 @@ static void time_dense(const char* what, const dense::DenseArgs& g, double flops
   CHECK(hipFuncSetAttribute((const void*)kclk, hipFuncAttributeMaxDynamicSharedMemorySize, dense::LDS_BYTES));
   for (int i = 0; i < 10; ++i) hipLaunchKernelGGL(kclk, dim3(256), dim3(256), dense::LDS_BYTES, 0, g);
   CHECK(hipDeviceSynchronize());
-  static long long hc[2][1024];
+  static long long hc[4][1024];
   CHECK(hipMemcpyFromSymbol(hc, HIP_SYMBOL(dense::g_diag_cycles), sizeof(hc)));
-  double loop = 0, outc = 0;
+  double loop = 0, outc = 0, ticks = 0;
   for (int i = 0; i < 1024; ++i) {
     loop += (double)hc[0][i];
     outc += (double)hc[1][i];
+    ticks += (double)hc[2][i];
   }
-  printf("  %-58s %.3f ms  %7.1f TFLOP/s   %6.0f cycles per 32-deep stage (32 MFMAs = 1024), %5.0f per tile output\n", what, ms, flops / ms / 1e9,
-         loop / 1024 / g.ktiles, outc / 1024);
+  // workgroup w runs on XCD w % 8: mean life of a workgroup per XCD, fastest and slowest XCD
+  double xmin = 1e30, xmax = 0;
+  for (int x = 0; x < 8; ++x) {
+    double d = 0;
+    for (int w = x; w < 256; w += 8) d += (double)hc[3][w * 4];
+    d /= 32 * 100.0;
+    xmin = fmin(xmin, d);
+    xmax = fmax(xmax, d);
+  }
+  printf("  %-58s %.3f ms  %7.1f TFLOP/s   %6.0f cycles per 32-deep stage (32 MFMAs = 1024), %5.0f per tile output, %.2f GHz, "
+         "workgroups live %.0f-%.0f us by XCD\n", what, ms, flops / ms / 1e9, loop / 1024 / g.ktiles, outc / 1024, loop / ticks / 10.0, xmin, xmax);
 }
 
 int main() {
@@ -221,6 +231,11 @@ int main() {
       maxref = fmax(maxref, fabs(r));
     }
     printf("  spot check of the forward product: max |err| %.4g on max |ref| %.4g\n", maxerr, maxref);
+    // the same kernels on zero operands: the same cycles at the clock the power limit then allows
+    CHECK(hipMemset(dW, 0, hW.size() * 2));
+    CHECK(hipMemset(dA, 0, hA.size() * 2));
+    time_dense<true, 0>("forward, all operands zero", g, flops);
+    time_dense<false, 0>("backward, all operands zero", g, flops);
   }
   return 0;
 }

@@ -69,8 +69,10 @@ __device__ inline void dma16g_s(int s, const void* sbase, uint32_t voff, uint32_
   }
 }
 
-// DIAG bit 3: cycle counts of this workgroup's second tile, per wave: [0] its main loop, [1] its output.
-static __device__ long long g_diag_cycles[2][4 * 256];
+// DIAG bit 3: counts of this workgroup's second tile, per wave: [0] core cycles of its main loop, [1] of its
+// output, [2] the main loop again in ticks of the constant 100 MHz counter (cycles / ticks = the clock the
+// CU ran at); [3] ticks from the wave's start to its end.
+static __device__ long long g_diag_cycles[4][4 * 256];
 
 // DIAG (measurement builds only; the library instantiates DIAG = 0): bit 0 stops the direct-to-LDS loads
 // after the prologue, bit 1 stops the fragment reads inside the loop, bit 2 keeps the load addresses on
@@ -83,6 +85,8 @@ __global__ __launch_bounds__(256) void dense_stream_kernel(DenseArgs g) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
+  long long t_start = 0;
+  if (DIAG & 8) t_start = __builtin_amdgcn_s_memrealtime();
 
   // ---- this workgroup's tiles.  Workgroups go to the 8 XCDs round robin; in every step of
   // gridDim.x tiles each XCD takes a contiguous run of the tile order (GROUP tile rows walked
@@ -250,8 +254,11 @@ __global__ __launch_bounds__(256) void dense_stream_kernel(DenseArgs g) {
   auto run = [&](auto WC) {
     constexpr int W = decltype(WC)::value;
     for (int ti = 0; ti < n_my; ++ti) {
-      long long tc0 = 0, tc1 = 0;
-      if ((DIAG & 8) && ti == 1) tc0 = __builtin_readcyclecounter();
+      long long tc0 = 0, tc1 = 0, tr0 = 0, tr1 = 0;
+      if ((DIAG & 8) && ti == 1) {
+        tc0 = __builtin_readcyclecounter();
+        tr0 = __builtin_amdgcn_s_memrealtime();
+      }
       for (int kt = 0; kt < KT; ++kt) {
         const char* stage = lds + cslot * STAGE_BYTES;
         // k step 0 from F; fetch k step 1 of this stage; B half of the stage in issue (its A half
@@ -281,7 +288,10 @@ __global__ __launch_bounds__(256) void dense_stream_kernel(DenseArgs g) {
         }
         cslot = nslot;
       }
-      if ((DIAG & 8) && ti == 1) tc1 = __builtin_readcyclecounter();
+      if ((DIAG & 8) && ti == 1) {
+        tc1 = __builtin_readcyclecounter();
+        tr1 = __builtin_amdgcn_s_memrealtime();
+      }
       // ---- tile done: round to bf16 and store, clear the accumulators.  The accumulator layout gives a
       // lane 4 consecutive columns of its row per register group; swapping groups between the lane halves
       // (v_permlane32_swap: the upper half of its first operand against the lower half of its second)
@@ -330,6 +340,7 @@ __global__ __launch_bounds__(256) void dense_stream_kernel(DenseArgs g) {
       if ((DIAG & 8) && ti == 1 && lane == 0 && blockIdx.x < 256) {
         g_diag_cycles[0][blockIdx.x * 4 + W] = tc1 - tc0;
         g_diag_cycles[1][blockIdx.x * 4 + W] = __builtin_readcyclecounter() - tc1;
+        g_diag_cycles[2][blockIdx.x * 4 + W] = tr1 - tr0;
       }
     }
   };
@@ -340,6 +351,7 @@ __global__ __launch_bounds__(256) void dense_stream_kernel(DenseArgs g) {
     default: run(std::integral_constant<int, 3>{}); break;
   }
   mm::wait_vmcnt_and_barrier<0>();   // the re-fetched stages land before the LDS is released
+  if ((DIAG & 8) && lane == 0 && blockIdx.x < 256) g_diag_cycles[3][blockIdx.x * 4 + wave] = __builtin_amdgcn_s_memrealtime() - t_start;
 }
 
 
