@@ -35,6 +35,8 @@ def parse():
                          "permutations every step), llama1b; or `micro`: the shapes of the paper's kernel tables "
                          "(permutation, block-diagonal product, Cayley-Neumann build) on the library's entry points; "
                          "or `vendor-gemm`: torch.matmul on the layer's dense shapes, as a reference for the dense kernel")
+    ap.add_argument("--xq-fused", action="store_true",
+                    help="with --variant xq: the dense products convert the INT8 codes themselves (no dequantised copy in the workspace)")
     ap.add_argument("--variant", default="fast", choices=["fast", "mem", "xq"],
                     help="fast keeps B from the forward pass (the measured metric); mem recomputes it in backward; "
                          "xq is mem on an INT8 base weight that every dense product dequantises first")
@@ -259,6 +261,8 @@ def run_workload(args, torch, px, get_config):
     ws_bytes = cnp_bytes = 0
     for p in projs:
         flags = {"fast": 0, "mem": px.FLAG_RECOMPUTE_B, "xq": px.FLAG_RECOMPUTE_B | px.FLAG_W_INT8}[args.variant]
+        if args.xq_fused and args.variant == "xq":
+            flags |= px.FLAG_W_INT8_FUSED
         if layer_series:
             flags |= px.FLAG_BLOCK_GRADS
         p["desc"] = px.make_desc(p["m"], p["n"], b, k, N, code, flags=flags,
@@ -303,7 +307,8 @@ def run_workload(args, torch, px, get_config):
             dXp = p["dX_tm"] if args.layout == "token" else dX[:m]
             px.poetx_linear_fwd(p["desc"], p["X"], p["W"], p["pi_R"], p["pi_P"], p["blk_R"], p["blk_P"],
                                 Zp, None if args.variant != "fast" else B[:n], ws)
-            if args.variant != "fast":
+            keep = args.variant == "fast"
+            if not keep and args.two_call_backward:   # the one-call backward recomputes B itself
                 px.poetx_linear_recompute_b(p["desc"], p["X"], p["W"], p["pi_R"], p["blk_R"], B[:n], ws)
             if args.two_call_backward:
                 px.poetx_linear_bwd_input(p["desc"], p["dZ"], p["W"], p["pi_R"], p["pi_P"], p["blk_R"], p["blk_P"],
@@ -311,7 +316,7 @@ def run_workload(args, torch, px, get_config):
                 px.poetx_linear_bwd_skew(p["desc"], p["X"], p["dZ"], B[:n], dA[:m], p["pi_R"], p["pi_P"],
                                          p["theta_R"], p["theta_P"], p["dtheta_R"], p["dtheta_P"], False, ws)
             else:   # the whole backward pass in one call: each side's gradient is streamed once
-                px.poetx_linear_bwd(p["desc"], p["X"], p["dZ"], B[:n], p["W"], p["pi_R"], p["pi_P"], p["blk_R"],
+                px.poetx_linear_bwd(p["desc"], p["X"], p["dZ"], B[:n] if keep else None, p["W"], p["pi_R"], p["pi_P"], p["blk_R"],
                                     p["blk_P"], p["theta_R"], p["theta_P"], dXp,
                                     p["dG_R"] if layer_series else p["dtheta_R"],
                                     p["dG_P"] if layer_series else p["dtheta_P"], False, ws)

@@ -114,8 +114,9 @@ typedef struct {
 
 /* Memory-saving variant (Sec. 3.5, POET-X_mem): the forward pass keeps no activation
  * (poetx_linear_fwd is called with saved_B = NULL and holds B in the workspace only) and the
- * backward pass recomputes A = R^T X and B = W A with poetx_linear_recompute_b before
- * poetx_linear_bwd_skew.  The flag sizes the workspace for that. */
+ * backward pass recomputes A = R^T X and B = W A: poetx_linear_bwd does so itself when it is called
+ * with saved_B = NULL (B then lives at the end of the workspace), and poetx_linear_recompute_b does it
+ * for callers of the two halves, before poetx_linear_bwd_skew.  The flag sizes the workspace for that. */
 #define POETX_FLAG_RECOMPUTE_B 1
 
 /* Quantised base weight (Sec. 3.6, POET-XQ): the frozen W is stored as signed 8-bit codes and
@@ -127,15 +128,23 @@ typedef struct {
  * A quantised weight buffer is int8 q[n][m] row major followed, at byte offset
  * (n*m rounded up to 256), by float scale[n]; poetx_weight_q8_bytes gives its size.
  * With this flag the W argument of poetx_linear_fwd, poetx_linear_recompute_b,
- * poetx_linear_bwd_input and poetx_linear_bwd is such a buffer.  For bf16 layers whose dimensions
- * are multiples of 256 the dense products read the codes themselves: code tiles and row scales
- * stream into LDS and are converted to bf16(scale * q) there, two stages ahead of the
- * multiplication, so no high-precision weight is ever written to memory and the workspace is that of
- * the plain memory-saving variant.  Other shapes and fp32 layers dequantise into the workspace
- * (one n x m weight more) right before each dense product; the values are the same bit for bit.
+ * poetx_linear_bwd_input and poetx_linear_bwd is such a buffer.  Each call dequantises it into its
+ * workspace (one n x m weight of the layer's dtype more, transient like the rest of the workspace) ahead
+ * of its dense products -- once per call: poetx_linear_bwd with saved_B = NULL uses the one copy for
+ * the recomputation of B and for dA = W^T dB.  That pass moves 3 bytes per weight element and is the
+ * fastest way through (about 2 % over the plain memory-saving variant at 16384 tokens).
  * As in the paper the flag is only valid together with POETX_FLAG_RECOMPUTE_B (the variant that
  * keeps no activation); alone it is POETX_ERR_INVALID_ARG. */
 #define POETX_FLAG_W_INT8 2
+
+/* With POETX_FLAG_W_INT8: the dense products read the codes themselves, for bf16 layers whose
+ * dimensions are multiples of 256 (other shapes and fp32 layers ignore the flag).  Code tiles and row
+ * scales stream into LDS and are converted to bf16(scale * q) there, two stages ahead of the
+ * multiplication, so no high-precision weight is ever written to memory and the workspace is that of
+ * the plain memory-saving variant -- for callers to whom one weight's worth of workspace matters more
+ * than the conversion work, which makes these products about 20 % slower.  The values are the same
+ * bit for bit either way.  Without POETX_FLAG_W_INT8 the flag is POETX_ERR_INVALID_ARG. */
+#define POETX_FLAG_W_INT8_FUSED 8
 
 /* Deferred series backward: poetx_linear_bwd_skew and poetx_linear_bwd stop after the block
  * gradients (Sec. 3.5: dG_P^j = B'_j dZ'_j^T, dG_R^j = X'_j dA'_j^T) and write them where they
@@ -170,7 +179,7 @@ typedef enum {
   POETX_STAGE_CNP_BWD = 4,    /* series backward + packed projection             */
   POETX_STAGE_APPLY_GRAD = 5, /* poetx_linear_bwd: structured product and block gradient of a side in one pass */
   POETX_STAGE_LAYOUT = 6,     /* token-major <-> feature-major passes            */
-  POETX_STAGE_DEQUANT = 7,    /* INT8 weight dequantised into the workspace (shapes the fused kernel does not cover) */
+  POETX_STAGE_DEQUANT = 7,    /* INT8 weight dequantised into the workspace */
   POETX_STAGE_COUNT = 8
 } poetx_stage;
 int poetx_profile_begin(int32_t max_records);
@@ -277,7 +286,7 @@ size_t poetx_linear_workspace_bytes(const poetx_linear_desc* desc);
 #define POETX_PATH_SERIES 8             /* series backward on the matrix cores                 */
 #define POETX_PATH_SERIES_ON_CHIP 16    /* ... as one-launch chains with the block in LDS      */
 #define POETX_PATH_BWD_ONE_PASS 32      /* poetx_linear_bwd streams each side's gradient once  */
-#define POETX_PATH_W_INT8_IN_KERNEL 64  /* POETX_FLAG_W_INT8 converted inside the dense kernels */
+#define POETX_PATH_W_INT8_IN_KERNEL 64  /* POETX_FLAG_W_INT8_FUSED honoured: codes converted inside the dense kernels */
 int poetx_linear_path(const poetx_linear_desc* desc);
 
 /* X: m x N.  W: n x m.  blocks_R / blocks_P: block storage of the dtype (see top)
@@ -324,7 +333,10 @@ int poetx_linear_bwd_skew(const poetx_linear_desc* desc, const void* X, const vo
  * for the product and another for the block gradient.  Otherwise it runs the two halves as they are.
  * The block gradients are summed over token ranges in a fixed order, so results are reproducible
  * run to run; they differ from the two-call results only by that summation order.
- * Arguments as in the two halves; W follows desc->flags (POETX_FLAG_W_INT8). */
+ * Arguments as in the two halves; W follows desc->flags (POETX_FLAG_W_INT8).  saved_B may be NULL when
+ * desc->flags has POETX_FLAG_RECOMPUTE_B: the call then recomputes B = W (R^T X) first, with the kernels
+ * and the rounding of poetx_linear_fwd, so every result is the one poetx_linear_recompute_b followed by
+ * this call would give, bit for bit. */
 int poetx_linear_bwd(const poetx_linear_desc* desc, const void* X, const void* dZ, const void* saved_B,
                      const void* W, const int32_t* perm_R, const int32_t* perm_P,
                      const void* blocks_R, const void* blocks_P,

@@ -19,6 +19,7 @@ F32, BF16 = 0, 1
 CNP_FP32, CNP_BF16 = 0, 1
 FLAG_RECOMPUTE_B = 1
 FLAG_W_INT8 = 2
+FLAG_W_INT8_FUSED = 8
 FLAG_BLOCK_GRADS = 4
 FEATURE_MAJOR, TOKEN_MAJOR = 0, 1
 

@@ -53,9 +53,10 @@ int check_desc(const poetx_linear_desc* d) {
     return POETX_ERR_INVALID_ARG;
   if (!dtype_ok(d->dtype)) return POETX_ERR_INVALID_ARG;
   if (d->cnp_precision != POETX_CNP_FP32 && d->cnp_precision != POETX_CNP_BF16) return POETX_ERR_INVALID_ARG;
-  if ((d->flags & ~(POETX_FLAG_RECOMPUTE_B | POETX_FLAG_W_INT8 | POETX_FLAG_BLOCK_GRADS)) != 0 || (d->layout != POETX_FEATURE_MAJOR && d->layout != POETX_TOKEN_MAJOR))
+  if ((d->flags & ~(POETX_FLAG_RECOMPUTE_B | POETX_FLAG_W_INT8 | POETX_FLAG_BLOCK_GRADS | POETX_FLAG_W_INT8_FUSED)) != 0 || (d->layout != POETX_FEATURE_MAJOR && d->layout != POETX_TOKEN_MAJOR))
     return POETX_ERR_INVALID_ARG;
   if ((d->flags & POETX_FLAG_W_INT8) && !(d->flags & POETX_FLAG_RECOMPUTE_B)) return POETX_ERR_INVALID_ARG;
+  if ((d->flags & POETX_FLAG_W_INT8_FUSED) && !(d->flags & POETX_FLAG_W_INT8)) return POETX_ERR_INVALID_ARG;
   if (d->block > d->d_in || d->block > d->d_out) return POETX_ERR_BAD_SHAPE;
   if (d->n_tokens >= (1ll << 31) || (i64)d->n_tokens * (d->d_in > d->d_out ? d->d_in : d->d_out) >= (1ll << 40))
     return POETX_ERR_UNSUPPORTED;
@@ -95,10 +96,10 @@ void dense_dispatch(int dtype, int trans_w, const void* W, int n, int m, const v
   else fma_dense(dtype, trans_w, W, n, m, act, out, N, st);
 }
 
-// POET-XQ: can the dense kernels read the 8-bit weight directly (conversion inside the operand path)?
-// Otherwise the weight is dequantised into the workspace before each product.
+// POET-XQ: do the dense kernels read the 8-bit weight directly (conversion inside the operand path; asked for
+// with POETX_FLAG_W_INT8_FUSED)?  Otherwise the weight is dequantised into the workspace before the products.
 bool weight_in_kernel(const poetx_linear_desc* d) {
-  return (d->flags & POETX_FLAG_W_INT8) && use_mfma(d->dtype) && mfma_dense_q8_supported(d->d_out, d->d_in, d->n_tokens);
+  return (d->flags & POETX_FLAG_W_INT8) && (d->flags & POETX_FLAG_W_INT8_FUSED) && use_mfma(d->dtype) && mfma_dense_q8_supported(d->d_out, d->d_in, d->n_tokens);
 }
 
 size_t blockgrad_ws_bytes(int dtype, int d, i64 N, int b) {
@@ -348,6 +349,17 @@ class LayoutStaging {
   int n_out_;
 };
 
+// poetx_linear_bwd called without saved_B recomputes B itself: B, then the dequantised weight (kept for both
+// of the call's dense products), sit at the very end of the workspace.
+static size_t dequantised_weight_bytes(const poetx_linear_desc* desc) {
+  return ((desc->flags & POETX_FLAG_W_INT8) && !weight_in_kernel(desc))
+             ? align256((size_t)desc->d_out * desc->d_in * esize(desc->dtype)) : 0;
+}
+static size_t recompute_tail_bytes(const poetx_linear_desc* desc) {
+  if (!(desc->flags & POETX_FLAG_RECOMPUTE_B)) return 0;
+  return align256((size_t)desc->d_out * (size_t)desc->n_tokens * esize(desc->dtype)) + dequantised_weight_bytes(desc);
+}
+
 static size_t core_workspace_bytes(const poetx_linear_desc* desc) {
   size_t es = esize(desc->dtype);
   size_t N = (size_t)desc->n_tokens;
@@ -380,6 +392,7 @@ static size_t core_workspace_bytes(const poetx_linear_desc* desc) {
                             align256(chain * sizeof(float)) + tail;
     if (one_pass > bwd) bwd = one_pass;
   }
+  bwd += recompute_tail_bytes(desc);
   return w > bwd ? w : bwd;
 }
 
@@ -431,11 +444,11 @@ int poetx_linear_recompute_b(const poetx_linear_desc* desc, const void* X, const
 // dB = P dZ, dA = W^T dB, dX = R dA; ws holds dB (and the dequantised weight behind it)
 static void bwd_input_impl(const poetx_linear_desc* desc, const void* dZ, const void* W, const int32_t* perm_R,
                            const int32_t* perm_P, const void* blocks_R, const void* blocks_P, void* dX, void* dA,
-                           void* ws, hipStream_t st) {
+                           void* ws, hipStream_t st, const void* W_resolved = nullptr) {
   const int m = desc->d_in, n = desc->d_out, b = desc->block, dt = desc->dtype;
   const i64 N = desc->n_tokens;
   void* dB = ws;
-  W = resolve_weight(desc, W, (char*)ws + align256((size_t)n * N * esize(dt)), st);
+  W = W_resolved ? W_resolved : resolve_weight(desc, W, (char*)ws + align256((size_t)n * N * esize(dt)), st);
   apply_left_dispatch(dt, dZ, dB, n, N, N, perm_P, blocks_P, b, 0, st);  // dB = P dZ
   dense_dispatch(dt, 1, W, n, m, dB, dA, N, st, weight_in_kernel(desc));                        // dA = W^T dB
   apply_left_dispatch(dt, dA, dX, m, N, N, perm_R, blocks_R, b, 0, st);  // dX = R dA
@@ -570,9 +583,10 @@ int poetx_linear_bwd(const poetx_linear_desc* desc, const void* X, const void* d
                      int32_t accumulate, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_desc(desc);
   if (rc) return rc;
-  if (!X || !dZ || !saved_B || !W || !perm_R || !perm_P || !blocks_R || !blocks_P || !theta_R || !theta_P || !dX ||
+  if (!X || !dZ || !W || !perm_R || !perm_P || !blocks_R || !blocks_P || !theta_R || !theta_P || !dX ||
       !dtheta_R || !dtheta_P)
     return POETX_ERR_INVALID_ARG;
+  if (!saved_B && !(desc->flags & POETX_FLAG_RECOMPUTE_B)) return POETX_ERR_INVALID_ARG;
   if (!ws || ws_bytes < poetx_linear_workspace_bytes(desc)) return POETX_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)stream;
   const int m = desc->d_in, n = desc->d_out, b = desc->block, dt = desc->dtype, k = desc->neumann_k;
@@ -583,11 +597,23 @@ int poetx_linear_bwd(const poetx_linear_desc* desc, const void* X, const void* d
   dX = lay.out(dX, m);
   void* dA = ws;                                                   // m x N, lives until the R side is done
   char* rest = (char*)ws + align256((size_t)m * N * esize(dt));
+  const void* W_resolved = nullptr;
+  if (!saved_B) {
+    // Gradient checkpoint inside the call (Sec. 3.5, memory-saving variant): A = R^T X goes where dA will
+    // be, B = W A to the end of the workspace; a quantised weight is dequantised once for both products.
+    char* end = (char*)ws + core_workspace_bytes(desc);
+    char* w_keep = end - dequantised_weight_bytes(desc);
+    char* B_re = w_keep - align256((size_t)n * N * esize(dt));
+    W_resolved = resolve_weight(desc, W, w_keep, st);
+    apply_left_dispatch(dt, X, dA, m, N, N, perm_R, blocks_R, b, 1, st);
+    dense_dispatch(dt, 0, W_resolved, n, m, dA, B_re, N, st, weight_in_kernel(desc));
+    saved_B = B_re;
+  }
   const bool one_pass = desc->cnp_precision == POETX_CNP_BF16 && use_mfma(dt) && lds_cnp_supported(m, b) &&
                         lds_cnp_supported(n, b) && mfma_apply_grad_supported(m, N, N, b) &&
                         mfma_apply_grad_supported(n, N, N, b);
   if (!one_pass) {   // the same values through the two halves
-    bwd_input_impl(desc, dZ, W, perm_R, perm_P, blocks_R, blocks_P, dX, dA, rest, st);
+    bwd_input_impl(desc, dZ, W, perm_R, perm_P, blocks_R, blocks_P, dX, dA, rest, st, W_resolved);
     bwd_skew_impl(desc, X, dZ, saved_B, dA, perm_R, perm_P, theta_R, theta_P, dtheta_R, dtheta_P, accumulate, rest, st);
     lay.finish();
     return launch_status();
@@ -609,7 +635,7 @@ int poetx_linear_bwd(const poetx_linear_desc* desc, const void* X, const void* d
     StageTimer tm(POETX_STAGE_APPLY_GRAD, st);
     mfma_apply_grad(dZ, saved_B, dB, n, N, N, perm_P, blocks_P, 0, dG_P, part, st);
   }
-  W = resolve_weight(desc, W, part, st);   // the P side's partials are reduced by now (stream order): same space
+  W = W_resolved ? W_resolved : resolve_weight(desc, W, part, st);   // the P side's partials are reduced by now (stream order): same space
   dense_dispatch(dt, 1, W, n, m, dB, dA, N, st, weight_in_kernel(desc));
   {
     StageTimer tm(POETX_STAGE_APPLY_GRAD, st);

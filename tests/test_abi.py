@@ -78,20 +78,29 @@ def test_flag_and_quantised_weight_checks(clib):
     mem = px.make_desc(256, 512, 32, 4, 512, px.BF16, flags=px.FLAG_RECOMPUTE_B)
     xq = px.make_desc(256, 512, 32, 4, 512, px.BF16, flags=px.FLAG_RECOMPUTE_B | px.FLAG_W_INT8)
     only_q = px.make_desc(256, 512, 32, 4, 512, px.BF16, flags=px.FLAG_W_INT8)
-    unknown = px.make_desc(256, 512, 32, 4, 512, px.BF16, flags=8)
-    w_plain, w_mem, w_xq = (px.poetx_linear_workspace_bytes(d) for d in (plain, mem, xq))
+    xqf = px.make_desc(256, 512, 32, 4, 512, px.BF16, flags=px.FLAG_RECOMPUTE_B | px.FLAG_W_INT8 | px.FLAG_W_INT8_FUSED)
+    fused_alone = px.make_desc(256, 512, 32, 4, 512, px.BF16, flags=px.FLAG_RECOMPUTE_B | px.FLAG_W_INT8_FUSED)
+    unknown = px.make_desc(256, 512, 32, 4, 512, px.BF16, flags=16)
+    w_plain, w_mem, w_xq, w_xqf = (px.poetx_linear_workspace_bytes(d) for d in (plain, mem, xq, xqf))
     assert w_mem >= (256 + 512) * 512 * 2 and w_mem >= w_plain
-    # these shapes are covered by the product kernel that converts the codes itself: no dequantised weight
-    assert w_xq == w_mem
-    # a shape it does not cover keeps room for one dequantised weight behind the activations
-    xq2 = px.make_desc(96, 160, 32, 4, 512, px.BF16, flags=px.FLAG_RECOMPUTE_B | px.FLAG_W_INT8)
+    # the backward call that recomputes B itself keeps B (and the dequantised weight) behind everything else
+    assert w_mem >= (256 + 2 * 512) * 512 * 2
+    # the weight is dequantised into the workspace: room for one n x m weight more ...
+    assert w_xq >= w_mem + 512 * 256 * 2
+    # ... unless the product kernel that converts the codes itself is asked for (these shapes are covered by it)
+    assert w_xqf == w_mem
+    # a shape it does not cover keeps the dequantised weight whatever the flag says
+    xq2 = px.make_desc(96, 160, 32, 4, 512, px.BF16, flags=px.FLAG_RECOMPUTE_B | px.FLAG_W_INT8 | px.FLAG_W_INT8_FUSED)
     assert px.poetx_linear_workspace_bytes(xq2) >= (96 + 160) * 512 * 2 + 160 * 96 * 2
+    assert px.poetx_linear_workspace_bytes(fused_alone) == 0                     # nothing to fuse without the INT8 weight
     assert px.poetx_linear_workspace_bytes(only_q) == 0                          # INT8 weight needs the no-activation variant
     assert px.poetx_linear_workspace_bytes(unknown) == 0
     assert clib.poetx_linear_fwd(ctypes.byref(only_q), *([fake] * 9), 1 << 30, None) == 1
     # saved_B may be absent only in the memory-saving variant
     args = [fake] * 7 + [None, fake]
     assert clib.poetx_linear_fwd(ctypes.byref(plain), *args, 1 << 30, None) == 1
+    bargs = [fake, fake, None] + [fake] * 10 + [0, fake]
+    assert clib.poetx_linear_bwd(ctypes.byref(plain), *bargs, 1 << 30, None) == 1
     assert px.poetx_weight_q8_bytes(512, 256) >= 512 * 256 + 4 * 512
     assert px.poetx_weight_q8_bytes(0, 256) == 0
     assert clib.poetx_weight_quantize_q8(None, px.BF16, 8, 8, fake, None) == 1
@@ -111,5 +120,7 @@ def test_linear_path_query(clib):
     assert px.poetx_linear_path(px.make_desc(64, 64, 16, 3, 256, px.F32)) == 0
     assert px.poetx_linear_path(px.make_desc(512, 1376, 64, 4, 1024, px.BF16)) == 0
     xq = px.make_desc(4096, 4096, 256, 5, 16384, px.BF16, flags=px.FLAG_RECOMPUTE_B | px.FLAG_W_INT8)
-    assert px.poetx_linear_path(xq) == full | px.PATH_W_INT8_IN_KERNEL
+    assert px.poetx_linear_path(xq) == full                       # dequantised into the workspace
+    xqf = px.make_desc(4096, 4096, 256, 5, 16384, px.BF16, flags=px.FLAG_RECOMPUTE_B | px.FLAG_W_INT8 | px.FLAG_W_INT8_FUSED)
+    assert px.poetx_linear_path(xqf) == full | px.PATH_W_INT8_IN_KERNEL
     assert px.poetx_linear_path(px.make_desc(256, 256, 32, 0, 512, px.F32)) == -1     # k < 1

@@ -398,10 +398,27 @@ def test_mem_variant_matches_fast(lib, m, n, N, b, k, dtype):
     # and the same kernels as the fast variant, so bit for bit the same values
     assert torch.equal(Z, dev["Z"]) and torch.equal(B, dev["B"]) and torch.equal(dX, dev["dX"])
     assert np.array_equal(to_np(dR), fast["dtheta_R"]) and np.array_equal(to_np(dP), fast["dtheta_P"])
+    # the one-call backward recomputes B itself when it gets none: the results of the one-call backward on the
+    # recomputed B, bit for bit (same kernels, same summation order), and the oracle's
+    outs = []
+    for sb in (B, None):
+        dX1 = torch.full_like(dX, float("nan"))
+        dR1, dP1 = torch.full_like(dR, float("nan")), torch.full_like(dP, float("nan"))
+        ws.fill_(0xFF)                                   # nothing may depend on what a previous call left behind
+        lib.poetx_linear_bwd(desc, dev["X"], dev["dZ"], sb, dev["W"], dev["pi_R"], dev["pi_P"], dev["blk_R"],
+                             dev["blk_P"], dev["th_R"], dev["th_P"], dX1, dR1, dP1, False, ws)
+        torch.cuda.synchronize()
+        outs.append((dX1, dR1, dP1))
+    assert all(torch.equal(a, c) for a, c in zip(outs[0], outs[1]))
+    assert torch.equal(outs[1][0], dX)
+    assert rel_err(to_np(outs[1][1]), ref["dtheta_R"]) <= TOL[dtype] and rel_err(to_np(outs[1][2]), ref["dtheta_P"]) <= TOL[dtype]
     # without the flag a missing saved_B is refused on the host
     with pytest.raises(lib.PoetxError):
         lib.poetx_linear_fwd(dev["desc"], dev["X"], dev["W"], dev["pi_R"], dev["pi_P"], dev["blk_R"], dev["blk_P"],
                              Z, None, dev["ws"])
+    with pytest.raises(lib.PoetxError):
+        lib.poetx_linear_bwd(dev["desc"], dev["X"], dev["dZ"], None, dev["W"], dev["pi_R"], dev["pi_P"], dev["blk_R"],
+                             dev["blk_P"], dev["th_R"], dev["th_P"], dX, dR, dP, False, dev["ws"])
 
 
 # ------------------------------------------------------------------ quantised base weight (POET-XQ)
@@ -438,9 +455,12 @@ def test_weight_q8_codes_bit_exact(lib, n, m, dtype):
 @pytest.mark.parametrize("m,n,N,b,k,dtype", [(256, 512, 256, 256, 4, "bf16"), (1376, 512, 384, 64, 4, "bf16"),
                                              (96, 160, 128, 32, 3, "f32"), (512, 768, 512, 256, 5, "bf16"),
                                              (1024, 256, 1280, 256, 3, "bf16"), (768, 2048, 768, 256, 2, "bf16")])
-def test_xq_layer(lib, m, n, N, b, k, dtype):
+@pytest.mark.parametrize("fused", [False, True])
+def test_xq_layer(lib, m, n, N, b, k, dtype, fused):
     """Memory-saving variant on an INT8 base weight: every product must be the oracle's on the
-    dequantised weight scale_i * q[i][k] (the oracle quantises with its own routine)."""
+    dequantised weight scale_i * q[i][k] (the oracle quantises with its own routine) -- with the weight
+    dequantised into the workspace ahead of the products, and with the products converting the codes
+    themselves (fused)."""
     data = synth_layer(9700 + m + n, m, n, N, b, k, dtype)
     q_ref, s_ref = orc.weight_quantize_q8(data["W"])
     ref = orc.linear_fwd_bwd_from_theta(data["X"], data["dZ"], orc.weight_dequantize_q8(q_ref, s_ref), data["pi_R"],
@@ -460,10 +480,13 @@ def test_xq_layer(lib, m, n, N, b, k, dtype):
     with pytest.raises(lib.PoetxError):
         lib.poetx_linear_fwd(bad, X, Wq, pi_R, pi_P, blk_R, blk_P, torch.empty((n, N), dtype=dt, device="cuda"),
                              torch.empty((n, N), dtype=dt, device="cuda"), ws_tensor(1 << 24))
-    desc = lib.make_desc(m, n, b, k, N, code, flags=lib.FLAG_RECOMPUTE_B | lib.FLAG_W_INT8)
+    lone = lib.make_desc(m, n, b, k, N, code, flags=lib.FLAG_RECOMPUTE_B | lib.FLAG_W_INT8_FUSED)   # nothing to fuse
+    assert lib.poetx_linear_workspace_bytes(lone) == 0
+    desc = lib.make_desc(m, n, b, k, N, code, flags=lib.FLAG_RECOMPUTE_B | lib.FLAG_W_INT8 | (lib.FLAG_W_INT8_FUSED if fused else 0))
     plain = lib.make_desc(m, n, b, k, N, code, flags=lib.FLAG_RECOMPUTE_B)
     es = 4 if dtype == "f32" else 2
-    in_kernel = dtype == "bf16" and m % 256 == 0 and n % 256 == 0 and N % 256 == 0
+    in_kernel = fused and dtype == "bf16" and m % 256 == 0 and n % 256 == 0 and N % 256 == 0
+    assert bool(lib.poetx_linear_path(desc) & lib.PATH_W_INT8_IN_KERNEL) == in_kernel
     if in_kernel:   # the dense kernels convert the codes themselves: no room for a high-precision weight
         assert lib.poetx_linear_workspace_bytes(desc) == lib.poetx_linear_workspace_bytes(plain)
     else:           # dequantised copy in the workspace
@@ -501,6 +524,13 @@ def test_xq_layer(lib, m, n, N, b, k, dtype):
     torch.cuda.synchronize()
     assert torch.equal(dX3, dX)
     assert rel_err(to_np(dR3), ref["dtheta_R"]) <= TOL[dtype] and rel_err(to_np(dP3), ref["dtheta_P"]) <= TOL[dtype]
+    # ... and with B recomputed inside the call (one dequantisation serves both of its products)
+    dX4 = torch.full_like(dX, float("nan"))
+    dR4, dP4 = torch.full_like(th_R, float("nan")), torch.full_like(th_P, float("nan"))
+    ws.fill_(0xFF)
+    lib.poetx_linear_bwd(desc, X, dZ, None, Wq, pi_R, pi_P, blk_R, blk_P, th_R, th_P, dX4, dR4, dP4, False, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dX4, dX3) and torch.equal(dR4, dR3) and torch.equal(dP4, dP3)
 
 
 # ------------------------------------------------------------------ stream capture
