@@ -728,5 +728,12 @@ def test_token_major_layout(lib, m, n, N, b, k, dtype):
     lib.poetx_linear_recompute_b(mem, Xt, dev["W"], dev["pi_R"], dev["blk_R"], B2, wsm)
     torch.cuda.synchronize()
     assert torch.equal(B2, dev["B"])
+    # ... and the one-call backward that recomputes B itself, from token-major X and dZ
+    dXt2 = torch.full((N, m), float("nan"), dtype=Xt.dtype, device="cuda")
+    dR2, dP2 = torch.full_like(dev["th_R"], float("nan")), torch.full_like(dev["th_P"], float("nan"))
+    lib.poetx_linear_bwd(mem, Xt, dZt, None, dev["W"], dev["pi_R"], dev["pi_P"], dev["blk_R"], dev["blk_P"],
+                         dev["th_R"], dev["th_P"], dXt2, dR2, dP2, False, wsm)
+    torch.cuda.synchronize()
+    assert torch.equal(dXt2, dXt1) and torch.equal(dR2, dR1) and torch.equal(dP2, dP1)
     # a layout code that does not exist is refused on the host
     assert lib.poetx_linear_workspace_bytes(lib.make_desc(m, n, b, k, N, code, layout=2)) == 0
