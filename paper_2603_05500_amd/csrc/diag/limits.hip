@@ -92,6 +92,20 @@ __global__ __launch_bounds__(256) void mfma16_loop_kernel(const bf16x8* __restri
   out[tid] = s;
 }
 
+// the same copy with one contiguous piece per workgroup (16 KB per pass): fewer, longer streams
+__global__ __launch_bounds__(256) void copy_chunk_kernel(const float4* __restrict__ in, float4* __restrict__ out, size_t n4) {
+  const size_t per = n4 / gridDim.x;
+  const float4* a = in + per * blockIdx.x;
+  float4* b = out + per * blockIdx.x;
+  for (size_t i = threadIdx.x; i + 768 < per; i += 1024) {
+    const float4 v0 = a[i], v1 = a[i + 256], v2 = a[i + 512], v3 = a[i + 768];
+    b[i] = v0;
+    b[i + 256] = v1;
+    b[i + 512] = v2;
+    b[i + 768] = v3;
+  }
+}
+
 __global__ void copy_kernel(const float4* __restrict__ in, float4* __restrict__ out, size_t n4) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -188,6 +202,8 @@ int main() {
     CHECK(hipMemset(a, 1, bytes));
     const float ms = sustained_ms([&] { hipLaunchKernelGGL(copy_kernel, dim3(256 * 16), dim3(256), 0, 0, a, b, bytes / 16); }, 20, 20);
     printf("2. device-to-device copy of 1 GiB: %.3f ms, %.0f GB/s read + write\n", ms, 2.0 * bytes / ms / 1e6);
+    const float msc = sustained_ms([&] { hipLaunchKernelGGL(copy_chunk_kernel, dim3(2048), dim3(256), 0, 0, a, b, bytes / 16); }, 20, 20);
+    printf("   the same with one contiguous 512 KB piece per workgroup: %.3f ms, %.0f GB/s\n", msc, 2.0 * bytes / msc / 1e6);
     CHECK(hipFree(a));
     CHECK(hipFree(b));
   }
