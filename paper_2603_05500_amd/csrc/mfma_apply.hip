@@ -349,10 +349,7 @@ void launch_apply_stream(const uint16_t* V, uint16_t* out, int d, i64 cols, i64 
   else
     hipLaunchKernelGGL(kern, dim3(chunks * MSPLIT, nb), dim3(512), LDS, st, V, out, ld, perm, E, trans, tiles / chunks, 0);
 }
-#ifndef SBN256_OVERRIDE
-#define SBN256_OVERRIDE 128
-#endif
-constexpr int SBN256 = SBN256_OVERRIDE, SBN512 = 64;
+constexpr int SBN256 = 128, SBN512 = 64;   // tokens per tile of the streaming kernel
 
 template <int B, int BN>
 void launch_apply(const uint16_t* V, uint16_t* out, int d, i64 cols, i64 ld, const int32_t* perm, const uint16_t* E,
